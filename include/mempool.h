@@ -1,0 +1,193 @@
+/*
+ * mempool.h -- C ABI of libmempool: MI355X-native movement of paged KV-cache blocks.
+ *
+ * The calls follow the Elastic Memory Pool API of the MemServe paper (Table 1:
+ * alloc_mem, free_mem, insert, match, swap_out / swap_in, transfer, transfer_with_insert;
+ * Table 3 adds evict).  Two "inference instances" of the paper are two pool handles in one
+ * process, so the paper's destination instance id becomes a destination pool handle.
+ *
+ * GEOMETRY (paper section 5.2, "Memory and Network Optimization")
+ *   L = n_layers, H = n_kv_heads, D = head_dim, bs = block_size (tokens), e = elem_bytes.
+ *   fragment   : the KV of bs tokens for ONE layer and ONE of {K,V}: F = bs*H*D*e bytes,
+ *                contiguous.  This is the engine's "block"; bs tokens need 2*L of them.
+ *   record     : the 2*L fragments of one run of bs tokens laid end to end, B = 2*L*F bytes.
+ *                This is the paper's aggregated block.
+ *   HBM pool   (MP_TIER_HBM, "discrete" layout)  : [L][2][NB][F] bytes; fragment (l,kv,b)
+ *                starts at byte ((l*2+kv)*NB + b)*F of `base`.
+ *   host pool  (MP_TIER_HOST_PINNED, aggregated) : [NB][L][2][F] bytes; block b is the
+ *                contiguous record at byte b*B of `base`.
+ *   staging    : [n][L][2][F] bytes, record i (the i-th entry of a block table) at i*B.
+ *   F must be a multiple of 16 bytes.  The copy never looks inside a fragment.
+ *
+ * MEMORY OWNERSHIP
+ *   The caller owns `base` and `staging` (for an HBM pool: device memory, e.g. a torch tensor's
+ *   data_ptr; for a host pool: pinned host memory) and keeps them alive and 16-byte aligned
+ *   until mp_pool_destroy.  The library owns the handle, the host-side index / free list /
+ *   reference counts, small device + pinned buffers for block tables, tokens and hashes, one
+ *   side stream for host-tier copies, and a few events.  Every pointer argument of every call
+ *   below is a HOST pointer unless its comment says "device".
+ *
+ * BLOCK LIFE CYCLE (paper section 4.1: active vs historical KV cache)
+ *   FREE --mp_alloc--> held (ref = 1) --mp_insert--> held + indexed --mp_free--> ref - 1;
+ *   at ref 0 an indexed block is HISTORICAL (evictable), a non-indexed one returns to FREE.
+ *   mp_evict turns HISTORICAL leaf blocks into FREE ones.  mp_match(MP_MATCH_PIN) adds one
+ *   reference per returned block (dropped again with mp_free).
+ *   The free list is a LIFO stack: a fresh pool hands out 0,1,2,...; freed / evicted ids are
+ *   pushed in the order they are released.
+ *
+ * ERRORS
+ *   Every call returns MP_OK (0) or a negative code.  Calls are all-or-nothing: when a code
+ *   other than MP_OK or MP_EHIP comes back, no pool byte, index entry, reference count or
+ *   free-list entry has changed.  mp_last_error(pool) returns a text for the last failure.
+ *
+ * THREADS AND STREAMS
+ *   One thread at a time per pool.  Device work of a transfer is enqueued on the SOURCE pool's
+ *   stream (the sender executes the transmission, paper section 4.3); hashing for
+ *   match/insert runs on the stream of the pool whose index is consulted.  Without MP_ASYNC a
+ *   call returns after its device work has completed.
+ */
+#ifndef MEMPOOL_H
+#define MEMPOOL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct mp_pool mp_pool_t; /* opaque, library-owned */
+
+/* memory "type" of Table 1 */
+#define MP_TIER_HBM 0u
+#define MP_TIER_HOST_PINNED 1u
+
+/* return codes */
+#define MP_OK 0
+#define MP_EINVAL (-1)     /* null pointer, id out of range, id not held, duplicate dst id, ... */
+#define MP_ESHAPE (-2)     /* src / dst geometry differs (asymmetric parallelism unsupported) */
+#define MP_ENOMEM (-3)     /* destination cannot supply the requested number of blocks */
+#define MP_ENOSTAGING (-4) /* staging buffer missing or smaller than what the call needs */
+#define MP_EHIP (-5)       /* a HIP runtime call failed */
+#define MP_ESTALE (-6)     /* transfer_with_insert: blocks [0,first_block) not in dst index */
+
+/* flags (bitmask) */
+#define MP_DST_GIVEN 0x01u        /* caller supplies dst_blocks; allocation step skipped      */
+#define MP_EVICT_ON_DEMAND 0x02u  /* allocation may evict historical blocks to make room      */
+#define MP_ASYNC 0x04u            /* enqueue only; results valid in stream order              */
+#define MP_MATCH_PIN 0x08u        /* mp_match: take one reference on every returned block     */
+#define MP_TOKENS_ON_DEVICE 0x10u /* `tokens` is a device pointer (same device as the pool)   */
+#define MP_DIRECT 0x20u           /* HBM->HBM only: one fused kernel, no staging round trip   */
+
+typedef struct {
+  uint32_t n_layers, n_kv_heads, head_dim, block_size, elem_bytes;
+  uint32_t n_blocks;     /* NB */
+  uint32_t tier;         /* MP_TIER_HBM or MP_TIER_HOST_PINNED */
+  uint32_t instance_id;  /* kept in every index node (paper section 4.2, second extension) */
+  uint64_t hash_seed;    /* h_{-1} of the chained block hash */
+  void *base;            /* caller-owned pool memory, 2*L*NB*F bytes, 16-byte aligned */
+  void *staging;         /* caller-owned DEVICE buffer for records; may be NULL */
+  uint64_t staging_bytes;
+  void *stream;          /* hipStream_t; NULL = the default stream */
+} mp_pool_desc_t;
+
+typedef struct {
+  uint32_t n_blocks, n_free, n_held, n_indexed, n_historical;
+  uint64_t clock; /* logical LRU clock: +1 per index-touching call */
+} mp_pool_stats_t;
+
+/* Create / destroy a pool handle.  Never allocates or frees base / staging. */
+int mp_pool_create(const mp_pool_desc_t *desc, mp_pool_t **out);
+int mp_pool_destroy(mp_pool_t *p);
+int mp_pool_stats(mp_pool_t *p, mp_pool_stats_t *out);
+const char *mp_last_error(mp_pool_t *p); /* never NULL; valid until the next call on p */
+const char *mp_strerror(int code);
+
+/* alloc_mem / free_mem (Table 1, memory block APIs).  mp_alloc pops n ids (ref = 1 each);
+ * with MP_EVICT_ON_DEMAND it first evicts exactly the shortfall.  MP_ENOMEM if impossible.
+ * mp_free drops one reference per listed id (an id may be listed as often as it is
+ * referenced); MP_EINVAL if an id is out of range or not referenced that often. */
+int mp_alloc(mp_pool_t *p, uint32_t n, int32_t *blocks_out, uint32_t flags);
+int mp_free(mp_pool_t *p, const int32_t *blocks, uint32_t n);
+
+/* insert (Table 1): map each FULL block i < floor(n_tokens/bs) of the prompt to blocks[i].
+ * A prefix that is already indexed keeps its existing block (first writer wins; blocks[i]
+ * stays the caller's).  Blocks that get adopted must be held by the caller and not indexed
+ * elsewhere.  n_blocks >= floor(n_tokens/bs).  *n_new_out = number of nodes created. */
+int mp_insert(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, const int32_t *blocks,
+              uint32_t n_blocks, uint32_t flags, uint32_t *n_new_out);
+
+/* match (Table 1): longest indexed block-aligned prefix of the prompt, at most cap blocks.
+ * Writes the m block ids to blocks_out and m to *n_matched_out. */
+int mp_match(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, int32_t *blocks_out,
+             uint32_t cap, uint32_t *n_matched_out, uint32_t flags);
+
+/* evict (Table 3): up to n_blocks times, free the least recently used unreferenced LEAF of the
+ * index (ties: smallest block id).  *n_evicted_out may be smaller than n_blocks. */
+int mp_evict(mp_pool_t *p, uint32_t n_blocks, uint32_t *n_evicted_out);
+
+/* transfer (Table 1, section 4.3): allocate n blocks at dst (unless MP_DST_GIVEN), then copy
+ * block src_blocks[i] of src into block dst_blocks[i] of dst for all i (all 2*L fragments).
+ * HBM->HBM: gather into src's staging, scatter from it (or one fused kernel with MP_DIRECT).
+ * HBM->host: gather, then asynchronous device-to-host copies of records on the side stream.
+ * host->HBM: host-to-device copies into dst's staging, then scatter.
+ * Transfers larger than the staging buffer are cut into staging-sized rounds.
+ * src ids must be held or historical; given dst ids must be held and duplicate-free.
+ * priv / priv_len: opaque user data handed to the receiver callback, never sent to the GPU. */
+int mp_transfer(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks,
+                int32_t *dst_blocks /* in with MP_DST_GIVEN, else out */, uint32_t n,
+                uint32_t flags, const void *priv, uint64_t priv_len);
+
+/* transfer_with_insert (Table 1, section 4.3): transfer, then the receiver inserts the prompt.
+ * Blocks [0,first_block) of the prompt must already be in dst's index (else MP_ESTALE);
+ * src_blocks / dst_blocks describe prompt blocks first_block .. first_block+n-1, and
+ * first_block + n >= floor(n_tokens/bs).  A trailing partial block is copied, not indexed. */
+int mp_transfer_with_insert(mp_pool_t *src, mp_pool_t *dst, const uint32_t *tokens,
+                            uint32_t n_tokens, uint32_t first_block, const int32_t *src_blocks,
+                            int32_t *dst_blocks, uint32_t n, uint32_t flags, const void *priv,
+                            uint64_t priv_len);
+
+/* Batched forms: n_req prompts concatenated in `tokens`, prompt r = tokens[tok_off[r] ..
+ * tok_off[r+1]).  One hash launch / one copy launch per round for the whole batch. */
+int mp_match_batch(mp_pool_t *p, const uint32_t *tokens, const uint32_t *tok_off,
+                   uint32_t n_req, int32_t *blocks_out,
+                   const uint32_t *blk_off /* n_req+1: slot range of request r in blocks_out */,
+                   uint32_t *n_matched_out /* n_req */, uint32_t flags);
+int mp_transfer_with_insert_batch(mp_pool_t *src, mp_pool_t *dst, const uint32_t *tokens,
+                                  const uint32_t *tok_off, uint32_t n_req,
+                                  const uint32_t *first_block /* n_req */,
+                                  const int32_t *src_blocks, int32_t *dst_blocks,
+                                  const uint32_t *blk_off /* n_req+1 into both tables */,
+                                  uint32_t flags);
+
+/* Chained block hashes of one prompt (section 4.2 index key; the hash itself is this
+ * library's convention): out[i] for i < floor(n_tokens/bs), computed by the device kernel. */
+int mp_block_hashes(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, uint64_t *out,
+                    uint32_t flags);
+
+/* Data-plane pieces of a transfer, exposed for tests and measurement.  `tbl` are HOST arrays
+ * of n block ids; `staging` of the pool is the other end. */
+int mp_gather(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags);
+int mp_scatter(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags);
+
+/* Receiver callback for `priv` (paper: request id, sampling parameters, ...). */
+typedef void (*mp_recv_cb)(void *user, const void *priv, uint64_t priv_len,
+                           const int32_t *dst_blocks, uint32_t n);
+int mp_set_recv_callback(mp_pool_t *p, mp_recv_cb cb, void *user);
+
+/* Kernel timing with HIP events on the launch stream.  kind: 0 gather, 1 scatter, 2 direct,
+ * 3 block_hash.  mp_profile_read synchronises, returns total ms and launch count since the
+ * last read, and clears them. */
+int mp_profile_enable(mp_pool_t *p, int on);
+int mp_profile_read(mp_pool_t *p, int kind, double *total_ms_out, uint64_t *launches_out,
+                    uint64_t *bytes_out);
+
+/* Kernel launch-shape knobs (for tuning sweeps; defaults are chosen per geometry).
+ * key: "order" (0 record-major, 1 plane-major), "unroll" (1,2,4,8), "wg_per_cu" (0 = one
+ * workgroup per tile group, >0 = persistent grid of that many workgroups per CU),
+ * "nontemporal" (0/1). */
+int mp_set_tunable(mp_pool_t *p, const char *key, int value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* MEMPOOL_H */
