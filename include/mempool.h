@@ -164,6 +164,16 @@ int mp_transfer_with_insert_batch(mp_pool_t *src, mp_pool_t *dst, const uint32_t
 int mp_block_hashes(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, uint64_t *out,
                     uint32_t flags);
 
+/* Host-only forms of insert / match for callers that already hold the prompt's chained
+ * hashes (e.g. computed once by mp_block_hashes where the request entered the cluster and
+ * forwarded with it): hashes[i] for i < floor(n_tokens/bs).  No device work. */
+int mp_insert_hashed(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens,
+                     const uint64_t *hashes, const int32_t *blocks, uint32_t n_blocks,
+                     uint32_t flags, uint32_t *n_new_out);
+int mp_match_hashed(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens,
+                    const uint64_t *hashes, int32_t *blocks_out, uint32_t cap,
+                    uint32_t *n_matched_out, uint32_t flags);
+
 /* Data-plane pieces of a transfer, exposed for tests and measurement.  `tbl` are HOST arrays
  * of n block ids; `staging` of the pool is the other end. */
 int mp_gather(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags);
@@ -186,6 +196,10 @@ int mp_profile_read(mp_pool_t *p, int kind, double *total_ms_out, uint64_t *laun
  * workgroup per tile group, >0 = persistent grid of that many workgroups per CU),
  * "nontemporal" (0/1). */
 int mp_set_tunable(mp_pool_t *p, const char *key, int value);
+
+/* Host-only self check of internal integer arithmetic (multiply-shift division used for
+ * work-item decomposition).  Returns MP_OK or MP_EINVAL. */
+int mp_selftest(void);
 
 #ifdef __cplusplus
 }

@@ -1,0 +1,160 @@
+// kv_copy.hip -- block-table-driven copy of paged KV fragments on gfx950 (CDNA4).
+//
+// What it computes (paper section 5.2): bs tokens of KV live in 2*L discrete fragments of
+// F bytes, one per (layer, K|V) plane; a transfer moves, for every entry i of a block table,
+// all 2*L fragments between a pool and a contiguous record (the paper's aggregated block).
+// One launch covers every entry, layer and K/V plane of a request batch, instead of one
+// network call per discrete block as in the paper's NCCL path (section 7).
+//
+// Mapping to the machine: the path is pure data movement, so no MFMA and no LDS.  The unit of
+// work is a wave-item: one 64-lane wavefront moves U*1 KiB of one fragment with U 16-byte
+// loads per lane in flight before the first store.  Block ids are wave-uniform, so table
+// reads and all address arithmetic up to the lane offset run on the scalar unit; the item ->
+// (entry, plane, chunk) split uses multiply-shift division by launch invariants.
+#include "kv_copy.hpp"
+
+namespace mempool {
+
+FastDiv make_fastdiv(uint32_t d) {
+  FastDiv f;
+  f.d = d;
+  uint32_t l = 0;
+  while ((1ull << l) < d) ++l;  // l = ceil(log2 d)
+  f.s = 31 + l;
+  f.m = (uint32_t)(((1ull << f.s) + d - 1) / d);  // ceil(2^(31+l) / d) < 2^32
+  return f;
+}
+
+namespace {
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+struct CopyArgs {
+  const uint8_t *src_base;
+  uint8_t *dst_base;
+  uint64_t src_plane_stride, src_block_stride;
+  uint64_t dst_plane_stride, dst_block_stride;
+  uint32_t n_items;    // n * n_planes * chunks_per_frag  (< 2^31)
+  uint32_t frag_vecs;  // F / 16
+  uint32_t n_planes;
+  uint32_t n_entries;
+  FastDiv by_chunks;   // / chunks_per_frag
+  FastDiv by_inner;    // / n_planes (order 0) or / n_entries (order 1)
+};
+
+// The tables are separate restrict-qualified read-only arguments so that the wave-uniform
+// id loads can be issued as scalar loads.  (A table never aliases pool or staging memory.)
+template <int U, int ORDER, bool NT>
+__global__ __launch_bounds__(256) void kv_block_copy(const CopyArgs a,
+                                                     const int32_t *__restrict__ src_tbl,
+                                                     const int32_t *__restrict__ dst_tbl) {
+  const uint32_t lane = threadIdx.x & 63u;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t step = gridDim.x * 4u;
+  for (uint32_t item = blockIdx.x * 4u + wave; item < a.n_items; item += step) {
+    // wave-uniform decomposition: item = (outer * inner_count + inner) * chunks + c
+    const uint32_t q = fastdiv(item, a.by_chunks);
+    const uint32_t c = item - q * a.by_chunks.d;
+    const uint32_t o = fastdiv(q, a.by_inner);
+    const uint32_t r = q - o * a.by_inner.d;
+    const uint32_t i = ORDER == 0 ? o : r;  // table entry
+    const uint32_t p = ORDER == 0 ? r : o;  // plane = layer * 2 + (K|V)
+    const uint32_t sid = __builtin_amdgcn_readfirstlane(src_tbl ? (uint32_t)src_tbl[i] : i);
+    const uint32_t did = __builtin_amdgcn_readfirstlane(dst_tbl ? (uint32_t)dst_tbl[i] : i);
+    const u32x4 *s = reinterpret_cast<const u32x4 *>(a.src_base + p * a.src_plane_stride +
+                                                     sid * a.src_block_stride);
+    u32x4 *d = reinterpret_cast<u32x4 *>(a.dst_base + p * a.dst_plane_stride +
+                                         did * a.dst_block_stride);
+    const uint32_t v0 = c * (64u * U) + lane;
+    u32x4 reg[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t v = v0 + 64u * u;
+      if (v < a.frag_vecs) reg[u] = NT ? __builtin_nontemporal_load(s + v) : s[v];
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const uint32_t v = v0 + 64u * u;
+      if (v < a.frag_vecs) {
+        if (NT) __builtin_nontemporal_store(reg[u], d + v);
+        else d[v] = reg[u];
+      }
+    }
+  }
+}
+
+template <int U, int ORDER>
+hipError_t launch_nt(const CopyArgs &a, const int32_t *st, const int32_t *dt, bool nt, dim3 grid,
+                     hipStream_t stream) {
+  if (nt)
+    hipLaunchKernelGGL((kv_block_copy<U, ORDER, true>), grid, dim3(256), 0, stream, a, st, dt);
+  else
+    hipLaunchKernelGGL((kv_block_copy<U, ORDER, false>), grid, dim3(256), 0, stream, a, st, dt);
+  return hipGetLastError();
+}
+
+template <int U>
+hipError_t launch_order(const CopyArgs &a, const int32_t *st, const int32_t *dt, int order,
+                        bool nt, dim3 grid, hipStream_t stream) {
+  return order == 0 ? launch_nt<U, 0>(a, st, dt, nt, grid, stream)
+                    : launch_nt<U, 1>(a, st, dt, nt, grid, stream);
+}
+
+}  // namespace
+
+hipError_t launch_block_copy(const CopySide &src, const CopySide &dst, uint32_t n,
+                             uint32_t n_planes, uint64_t frag_bytes, const CopyTune &tune,
+                             int n_cus, hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  if (!src.base || !dst.base || n_planes == 0 || frag_bytes == 0 || (frag_bytes & 15u) ||
+      (frag_bytes >> 4) > 0x7fffffffull)
+    return hipErrorInvalidValue;
+  int U = tune.unroll;
+  if (U != 1 && U != 2 && U != 4 && U != 8) return hipErrorInvalidValue;
+  const uint32_t frag_vecs = (uint32_t)(frag_bytes >> 4);
+  while (U > 1 && 64u * (U / 2) >= frag_vecs) U /= 2;  // no wider than the fragment
+  const uint32_t chunks = (frag_vecs + 64u * U - 1) / (64u * U);
+  const uint64_t per_entry = (uint64_t)n_planes * chunks;
+
+  // keep every item index below 2^31: split very large tables into several launches
+  const uint32_t max_entries = (uint32_t)(0x7fffffffull / per_entry);
+  if (max_entries == 0) return hipErrorInvalidValue;
+
+  for (uint32_t first = 0; first < n; first += max_entries) {
+    const uint32_t cnt = (n - first < max_entries) ? n - first : max_entries;
+    CopyArgs a;
+    // a table-less side addresses entry i directly, so shift its base instead of its table
+    a.src_base = (const uint8_t *)src.base + (src.tbl ? 0 : (uint64_t)first * src.block_stride);
+    a.dst_base = (uint8_t *)dst.base + (dst.tbl ? 0 : (uint64_t)first * dst.block_stride);
+    const int32_t *st = src.tbl ? src.tbl + first : nullptr;
+    const int32_t *dt = dst.tbl ? dst.tbl + first : nullptr;
+    a.src_plane_stride = src.plane_stride;
+    a.src_block_stride = src.block_stride;
+    a.dst_plane_stride = dst.plane_stride;
+    a.dst_block_stride = dst.block_stride;
+    a.n_items = (uint32_t)(per_entry * cnt);
+    a.frag_vecs = frag_vecs;
+    a.n_planes = n_planes;
+    a.n_entries = cnt;
+    a.by_chunks = make_fastdiv(chunks);
+    a.by_inner = make_fastdiv(tune.order == 0 ? n_planes : cnt);
+    uint32_t wgs = (a.n_items + 3u) / 4u;
+    if (tune.wg_per_cu > 0) {
+      const uint64_t cap = (uint64_t)tune.wg_per_cu * (uint64_t)(n_cus > 0 ? n_cus : 256);
+      if (wgs > cap) wgs = (uint32_t)cap;
+    }
+    const dim3 grid(wgs);
+    const bool nt = tune.nontemporal != 0;
+    hipError_t e;
+    switch (U) {
+      case 1: e = launch_order<1>(a, st, dt, tune.order, nt, grid, stream); break;
+      case 2: e = launch_order<2>(a, st, dt, tune.order, nt, grid, stream); break;
+      case 4: e = launch_order<4>(a, st, dt, tune.order, nt, grid, stream); break;
+      default: e = launch_order<8>(a, st, dt, tune.order, nt, grid, stream); break;
+    }
+    if (e != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+}  // namespace mempool

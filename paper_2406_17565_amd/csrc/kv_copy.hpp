@@ -1,0 +1,54 @@
+// kv_copy.hpp -- host-side interface of the block-table copy kernel (gfx950).
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+namespace mempool {
+
+// One end of a block-table copy.  Fragment (plane p, entry i) starts at
+//   base + p * plane_stride + id(i) * block_stride,   id(i) = tbl ? tbl[i] : i.
+// An HBM pool ([L][2][NB][F], the discrete layout of the paper's section 5.2) has
+// plane_stride = NB*F and block_stride = F; staging and the aggregated host layout
+// ([n][L][2][F]) have plane_stride = F and block_stride = 2*L*F.
+struct CopySide {
+  void *base = nullptr;
+  const int32_t *tbl = nullptr;  // DEVICE pointer, or null for the identity
+  uint64_t plane_stride = 0;
+  uint64_t block_stride = 0;
+};
+
+struct CopyTune {
+  int order = 0;        // 0: walk records (entry-major), 1: walk planes (plane-major)
+  int unroll = 4;       // 16-byte loads in flight per lane: 1, 2, 4 or 8
+  int wg_per_cu = 0;    // 0: one pass, a workgroup per 4 wave-items; >0: persistent grid
+  int nontemporal = 1;  // stream past the caches
+};
+
+// Unsigned division by an invariant divisor for numerators below 2^31:
+// x / d == (x * m) >> s.
+struct FastDiv {
+  uint32_t d = 1, m = 0x80000000u, s = 31;
+};
+FastDiv make_fastdiv(uint32_t d);
+__host__ __device__ inline uint32_t fastdiv(uint32_t x, const FastDiv &f) {
+  return (uint32_t)(((uint64_t)x * f.m) >> f.s);
+}
+
+// Copies n entries x n_planes fragments of frag_bytes (a multiple of 16) from src to dst.
+// Enqueues on `stream`; returns the launch status.  n_cus sizes a persistent grid.
+hipError_t launch_block_copy(const CopySide &src, const CopySide &dst, uint32_t n,
+                             uint32_t n_planes, uint64_t frag_bytes, const CopyTune &tune,
+                             int n_cus, hipStream_t stream);
+
+// Chained block hashes for a batch of prompts (one workgroup per prompt).
+//   tokens  : device, all prompts concatenated
+//   tok_off : device, n_req+1 token offsets
+//   blk_off : device, n_req+1 output offsets (prefix sums of floor(len/bs))
+//   out     : device, blk_off[n_req] hashes
+hipError_t launch_block_hash(const uint32_t *tokens, const uint32_t *tok_off,
+                             const uint32_t *blk_off, uint32_t n_req, uint32_t bs, uint64_t seed,
+                             uint64_t *out, hipStream_t stream);
+
+}  // namespace mempool

@@ -1,0 +1,872 @@
+// mempool_api.hip -- the C ABI of libmempool (see include/mempool.h for the contract).
+//
+// Paper: Table 1 (MemPool API), section 4.3 (transfer = allocation, transmission, insertion;
+// an explicit destination list skips allocation; transfer_with_insert lets the receiver
+// insert locally), section 4.2 (index), section 5.2 (discrete vs aggregated layout).
+//
+// This file holds host orchestration only: argument checks, the order of the three steps,
+// table / token staging through pinned memory, stream and event plumbing.  All data movement
+// and hashing is done by the kernels in kv_copy.hip and block_hash.hip (plus hipMemcpyAsync
+// for the pinned-host tier).
+#include "../../include/mempool.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "kv_copy.hpp"
+#include "pool_index.hpp"
+
+using namespace mempool;
+
+namespace {
+
+enum ProfKind { kProfGather = 0, kProfScatter = 1, kProfDirect = 2, kProfHash = 3, kProfKinds = 4 };
+
+struct ProfRec {
+  int kind;
+  hipEvent_t start, stop;
+  uint64_t bytes;
+};
+
+// A device buffer with a pinned host mirror, grown on demand.
+struct MirrorBuf {
+  void *dev = nullptr;
+  void *host = nullptr;
+  size_t cap = 0;
+};
+
+struct DeviceCtx {
+  bool ready = false;
+  int device = 0;
+  int n_cus = 256;
+  hipStream_t stream = nullptr;  // the caller's stream (from the pool descriptor)
+  hipStream_t side = nullptr;    // library-owned, for pinned-host tier copies
+  MirrorBuf tables;              // [src ids][dst ids]
+  MirrorBuf tokens;              // concatenated prompts
+  MirrorBuf offsets;             // [tok_off][blk_off]
+  MirrorBuf hashes;
+  hipEvent_t tables_uploaded = nullptr;
+  bool tables_pending = false;
+  hipEvent_t slot_filled[2] = {nullptr, nullptr};   // main -> side (or side -> main)
+  hipEvent_t slot_drained[2] = {nullptr, nullptr};  // the other direction
+  bool slot_busy[2] = {false, false};
+  bool profiling = false;
+  std::vector<ProfRec> prof;
+  double prof_ms[kProfKinds] = {0, 0, 0, 0};
+  uint64_t prof_launches[kProfKinds] = {0, 0, 0, 0};
+  uint64_t prof_bytes[kProfKinds] = {0, 0, 0, 0};
+};
+
+}  // namespace
+
+struct mp_pool {
+  mp_pool_desc_t desc;
+  uint64_t F = 0, B = 0;
+  uint32_t P = 0;  // planes = 2*L
+  PoolIndex idx;
+  DeviceCtx dev;
+  CopyTune tune;
+  bool tune_order_set = false;
+  std::string err;
+  mp_recv_cb cb = nullptr;
+  void *cb_user = nullptr;
+  std::vector<uint64_t> host_hashes;  // scratch
+  std::vector<int32_t> scratch_ids;
+};
+
+namespace {
+
+int fail(mp_pool *p, int code, const char *msg) {
+  if (p) p->err = msg;
+  return code;
+}
+
+int fail_hip(mp_pool *p, hipError_t e, const char *where) {
+  if (p) p->err = std::string(where) + ": " + hipGetErrorString(e);
+  return MP_EHIP;
+}
+
+#define HIP_TRY(pool, expr)                                  \
+  do {                                                       \
+    hipError_t e_ = (expr);                                  \
+    if (e_ != hipSuccess) return fail_hip(pool, e_, #expr);  \
+  } while (0)
+
+bool same_geometry(const mp_pool *a, const mp_pool *b) {
+  return a->desc.n_layers == b->desc.n_layers && a->desc.n_kv_heads == b->desc.n_kv_heads &&
+         a->desc.head_dim == b->desc.head_dim && a->desc.block_size == b->desc.block_size &&
+         a->desc.elem_bytes == b->desc.elem_bytes;
+}
+
+// ---- device context ----------------------------------------------------------------------
+int ensure_device(mp_pool *p) {
+  DeviceCtx &d = p->dev;
+  if (d.ready) return MP_OK;
+  HIP_TRY(p, hipGetDevice(&d.device));
+  int cus = 0;
+  HIP_TRY(p, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, d.device));
+  d.n_cus = cus > 0 ? cus : 256;
+  d.stream = (hipStream_t)p->desc.stream;
+  HIP_TRY(p, hipStreamCreateWithFlags(&d.side, hipStreamNonBlocking));
+  HIP_TRY(p, hipEventCreateWithFlags(&d.tables_uploaded, hipEventDisableTiming));
+  for (int s = 0; s < 2; ++s) {
+    HIP_TRY(p, hipEventCreateWithFlags(&d.slot_filled[s], hipEventDisableTiming));
+    HIP_TRY(p, hipEventCreateWithFlags(&d.slot_drained[s], hipEventDisableTiming));
+  }
+  d.ready = true;
+  return MP_OK;
+}
+
+int reserve(mp_pool *p, MirrorBuf &b, size_t bytes) {
+  if (bytes <= b.cap) return MP_OK;
+  size_t cap = b.cap ? b.cap : 4096;
+  while (cap < bytes) cap *= 2;
+  // earlier work may still read the old buffers
+  HIP_TRY(p, hipStreamSynchronize(p->dev.stream));
+  if (b.dev) HIP_TRY(p, hipFree(b.dev));
+  if (b.host) HIP_TRY(p, hipHostFree(b.host));
+  b.dev = b.host = nullptr;
+  b.cap = 0;
+  HIP_TRY(p, hipMalloc(&b.dev, cap));
+  HIP_TRY(p, hipHostMalloc(&b.host, cap, hipHostMallocDefault));
+  b.cap = cap;
+  return MP_OK;
+}
+
+void release(MirrorBuf &b) {
+  if (b.dev) (void)hipFree(b.dev);
+  if (b.host) (void)hipHostFree(b.host);
+  b = MirrorBuf();
+}
+
+// ---- profiling ---------------------------------------------------------------------------
+struct ProfScope {
+  mp_pool *p;
+  ProfRec rec;
+  bool on;
+  ProfScope(mp_pool *pool, int kind, uint64_t bytes) : p(pool), on(pool->dev.profiling) {
+    if (!on) return;
+    rec.kind = kind;
+    rec.bytes = bytes;
+    if (hipEventCreate(&rec.start) != hipSuccess || hipEventCreate(&rec.stop) != hipSuccess) {
+      on = false;
+      return;
+    }
+    (void)hipEventRecord(rec.start, p->dev.stream);
+  }
+  ~ProfScope() {
+    if (!on) return;
+    (void)hipEventRecord(rec.stop, p->dev.stream);
+    p->dev.prof.push_back(rec);
+  }
+};
+
+void prof_drain(mp_pool *p) {
+  DeviceCtx &d = p->dev;
+  for (ProfRec &r : d.prof) {
+    float ms = 0.f;
+    if (hipEventSynchronize(r.stop) == hipSuccess &&
+        hipEventElapsedTime(&ms, r.start, r.stop) == hipSuccess) {
+      d.prof_ms[r.kind] += ms;
+      d.prof_launches[r.kind] += 1;
+      d.prof_bytes[r.kind] += r.bytes;
+    }
+    (void)hipEventDestroy(r.start);
+    (void)hipEventDestroy(r.stop);
+  }
+  d.prof.clear();
+}
+
+// ---- hashing through the device kernel ------------------------------------------------------
+// Computes the chained hashes of n_req prompts into p->dev.hashes.host; blk_off_out receives
+// the n_req+1 offsets into that array.  Host tokens are staged through pinned memory; device
+// tokens are also copied back, because index nodes keep (and compare) their tokens.
+// On return *host_tokens points at a host copy of all tokens.
+int device_hashes(mp_pool *p, const uint32_t *tokens, const uint32_t *tok_off, uint32_t n_req,
+                  bool on_device, std::vector<uint32_t> &blk_off_out,
+                  const uint32_t **host_tokens, const uint64_t **host_hashes) {
+  int rc = ensure_device(p);
+  if (rc != MP_OK) return rc;
+  DeviceCtx &d = p->dev;
+  const uint32_t bs = p->desc.block_size;
+  const uint32_t total_tok = tok_off[n_req];
+  blk_off_out.assign(n_req + 1, 0);
+  for (uint32_t r = 0; r < n_req; ++r)
+    blk_off_out[r + 1] = blk_off_out[r] + (tok_off[r + 1] - tok_off[r]) / bs;
+  const uint32_t total_blk = blk_off_out[n_req];
+  if ((rc = reserve(p, d.tokens, std::max<size_t>(4, 4ull * total_tok))) != MP_OK) return rc;
+  if ((rc = reserve(p, d.offsets, 8ull * (n_req + 1))) != MP_OK) return rc;
+  if ((rc = reserve(p, d.hashes, std::max<size_t>(8, 8ull * total_blk))) != MP_OK) return rc;
+  *host_tokens = on_device ? (const uint32_t *)d.tokens.host : tokens;
+  *host_hashes = (const uint64_t *)d.hashes.host;
+  if (total_blk == 0) return MP_OK;
+
+  uint32_t *h_off = (uint32_t *)d.offsets.host;
+  std::memcpy(h_off, tok_off, 4ull * (n_req + 1));
+  std::memcpy(h_off + n_req + 1, blk_off_out.data(), 4ull * (n_req + 1));
+  HIP_TRY(p, hipMemcpyAsync(d.offsets.dev, h_off, 8ull * (n_req + 1), hipMemcpyHostToDevice,
+                            d.stream));
+  const uint32_t *d_tok;
+  if (on_device) {
+    d_tok = tokens;
+    HIP_TRY(p, hipMemcpyAsync(d.tokens.host, tokens, 4ull * total_tok, hipMemcpyDeviceToHost,
+                              d.stream));
+  } else {
+    std::memcpy(d.tokens.host, tokens, 4ull * total_tok);
+    HIP_TRY(p, hipMemcpyAsync(d.tokens.dev, d.tokens.host, 4ull * total_tok,
+                              hipMemcpyHostToDevice, d.stream));
+    d_tok = (const uint32_t *)d.tokens.dev;
+  }
+  {
+    ProfScope ps(p, kProfHash, 4ull * bs * total_blk + 8ull * total_blk);
+    const uint32_t *d_off = (const uint32_t *)d.offsets.dev;
+    HIP_TRY(p, launch_block_hash(d_tok, d_off, d_off + n_req + 1, n_req, bs, p->desc.hash_seed,
+                                 (uint64_t *)d.hashes.dev, d.stream));
+  }
+  HIP_TRY(p, hipMemcpyAsync(d.hashes.host, d.hashes.dev, 8ull * total_blk, hipMemcpyDeviceToHost,
+                            d.stream));
+  HIP_TRY(p, hipStreamSynchronize(d.stream));
+  return MP_OK;
+}
+
+// ---- block-table upload -----------------------------------------------------------------------
+// Puts [src ids][dst ids] on the device of `x` (either may be null); device pointers come back.
+int upload_tables(mp_pool *x, const int32_t *src_ids, const int32_t *dst_ids, uint32_t n,
+                  const int32_t **d_src, const int32_t **d_dst) {
+  DeviceCtx &d = x->dev;
+  int rc = reserve(x, d.tables, std::max<size_t>(8, 8ull * n));
+  if (rc != MP_OK) return rc;
+  if (d.tables_pending) {  // a previous asynchronous call may still be reading the pinned copy
+    HIP_TRY(x, hipEventSynchronize(d.tables_uploaded));
+    d.tables_pending = false;
+  }
+  int32_t *h = (int32_t *)d.tables.host;
+  if (src_ids) std::memcpy(h, src_ids, 4ull * n);
+  if (dst_ids) std::memcpy(h + n, dst_ids, 4ull * n);
+  HIP_TRY(x, hipMemcpyAsync(d.tables.dev, h, 8ull * n, hipMemcpyHostToDevice, d.stream));
+  HIP_TRY(x, hipEventRecord(d.tables_uploaded, d.stream));
+  d.tables_pending = true;
+  *d_src = (const int32_t *)d.tables.dev;
+  *d_dst = (const int32_t *)d.tables.dev + n;
+  return MP_OK;
+}
+
+CopySide pool_side(const mp_pool *p, const int32_t *d_tbl) {
+  CopySide s;
+  s.base = p->desc.base;
+  s.tbl = d_tbl;
+  if (p->desc.tier == MP_TIER_HBM) {  // discrete layout [L][2][NB][F]
+    s.plane_stride = (uint64_t)p->desc.n_blocks * p->F;
+    s.block_stride = p->F;
+  } else {  // aggregated layout [NB][L][2][F]
+    s.plane_stride = p->F;
+    s.block_stride = p->B;
+  }
+  return s;
+}
+
+CopySide record_side(const mp_pool *p, void *base) {
+  CopySide s;
+  s.base = base;
+  s.tbl = nullptr;
+  s.plane_stride = p->F;
+  s.block_stride = p->B;
+  return s;
+}
+
+CopyTune effective_tune(const mp_pool *p) { return p->tune; }
+
+bool tables_overlap(const mp_pool *p, const int32_t *a, const int32_t *b, uint32_t n) {
+  std::vector<uint8_t> seen(p->desc.n_blocks, 0);
+  for (uint32_t i = 0; i < n; ++i) seen[a[i]] = 1;
+  for (uint32_t i = 0; i < n; ++i)
+    if (seen[b[i]]) return true;
+  return false;
+}
+
+// Which staging problems would the copy hit?  Checked before any state changes.
+int check_copy_feasible(mp_pool *src, mp_pool *dst, uint32_t n, uint32_t flags) {
+  const bool s_hbm = src->desc.tier == MP_TIER_HBM, d_hbm = dst->desc.tier == MP_TIER_HBM;
+  if (!s_hbm && !d_hbm) return fail(src, MP_ESHAPE, "host-to-host transfers are not supported");
+  if (flags & MP_DIRECT) {
+    if (!s_hbm || !d_hbm) return fail(src, MP_EINVAL, "MP_DIRECT needs two HBM pools");
+    return MP_OK;
+  }
+  if (n == 0) return MP_OK;
+  mp_pool *x = s_hbm ? src : dst;
+  if (!x->desc.staging || x->desc.staging_bytes < x->B)
+    return fail(src, MP_ENOSTAGING, "staging buffer missing or smaller than one record");
+  return MP_OK;
+}
+
+// The transmission step.  All ids are already validated.  Enqueues on the executing pool's
+// stream; the caller synchronises if it must.
+int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *dst_ids,
+             uint32_t n, uint32_t flags) {
+  if (n == 0) return MP_OK;
+  const bool s_hbm = src->desc.tier == MP_TIER_HBM, d_hbm = dst->desc.tier == MP_TIER_HBM;
+  mp_pool *x = s_hbm ? src : dst;  // the pool whose device context executes
+  int rc = ensure_device(x);
+  if (rc != MP_OK) return rc;
+  DeviceCtx &d = x->dev;
+  const CopyTune tune = effective_tune(x);
+  const uint64_t B = x->B;
+  const int32_t *d_src = nullptr, *d_dst = nullptr;
+  rc = upload_tables(x, s_hbm ? src_ids : nullptr, d_hbm ? dst_ids : nullptr, n, &d_src, &d_dst);
+  if (rc != MP_OK) return rc;
+
+  if (flags & MP_DIRECT) {  // one fused kernel: pool fragment -> pool fragment
+    ProfScope ps(x, kProfDirect, 2ull * n * B);
+    HIP_TRY(x, launch_block_copy(pool_side(src, d_src), pool_side(dst, d_dst), n, x->P, x->F,
+                                 tune, d.n_cus, d.stream));
+    return MP_OK;
+  }
+
+  uint8_t *staging = (uint8_t *)x->desc.staging;
+  if (s_hbm && d_hbm) {  // gather into records, scatter out of them, staging-sized rounds
+    const uint32_t cap = (uint32_t)std::min<uint64_t>(x->desc.staging_bytes / B, 0xffffffffu);
+    for (uint32_t first = 0; first < n; first += cap) {
+      const uint32_t cnt = std::min(cap, n - first);
+      {
+        ProfScope ps(x, kProfGather, 2ull * cnt * B);
+        HIP_TRY(x, launch_block_copy(pool_side(src, d_src + first), record_side(x, staging), cnt,
+                                     x->P, x->F, tune, d.n_cus, d.stream));
+      }
+      {
+        ProfScope ps(x, kProfScatter, 2ull * cnt * B);
+        HIP_TRY(x, launch_block_copy(record_side(x, staging), pool_side(dst, d_dst + first), cnt,
+                                     x->P, x->F, tune, d.n_cus, d.stream));
+      }
+    }
+    return MP_OK;
+  }
+
+  // One end is the pinned-host tier (aggregated layout: a block is one contiguous record).
+  // Two staging slots let the kernel of round k+1 overlap the host-link copies of round k.
+  uint32_t n_slots = 2;
+  uint64_t slot_bytes = (x->desc.staging_bytes / 2) / B * B;
+  if (slot_bytes == 0 || (uint64_t)n * B <= x->desc.staging_bytes / B * B) {
+    n_slots = 1;
+    slot_bytes = x->desc.staging_bytes / B * B;
+  }
+  const uint32_t cap = (uint32_t)std::min<uint64_t>(slot_bytes / B, 0xffffffffu);
+  uint8_t *host_base = (uint8_t *)(s_hbm ? dst : src)->desc.base;
+  const int32_t *host_ids = s_hbm ? dst_ids : src_ids;
+  uint32_t round = 0;
+  for (uint32_t first = 0; first < n; first += cap, ++round) {
+    const uint32_t cnt = std::min(cap, n - first);
+    const uint32_t s = round % n_slots;
+    uint8_t *slot = staging + (uint64_t)s * slot_bytes;
+    if (s_hbm) {  // HBM -> host: gather on the main stream, then device-to-host on the side stream
+      if (d.slot_busy[s]) HIP_TRY(x, hipStreamWaitEvent(d.stream, d.slot_drained[s], 0));
+      {
+        ProfScope ps(x, kProfGather, 2ull * cnt * B);
+        HIP_TRY(x, launch_block_copy(pool_side(src, d_src + first), record_side(x, slot), cnt,
+                                     x->P, x->F, tune, d.n_cus, d.stream));
+      }
+      HIP_TRY(x, hipEventRecord(d.slot_filled[s], d.stream));
+      HIP_TRY(x, hipStreamWaitEvent(d.side, d.slot_filled[s], 0));
+    } else {  // host -> HBM: wait until the scatter that last used this slot is done
+      if (d.slot_busy[s]) HIP_TRY(x, hipStreamWaitEvent(d.side, d.slot_drained[s], 0));
+    }
+    for (uint32_t i = 0; i < cnt;) {  // one copy per run of consecutive host block ids
+      uint32_t j = i + 1;
+      while (j < cnt && host_ids[first + j] == host_ids[first + j - 1] + 1) ++j;
+      uint8_t *h = host_base + (uint64_t)host_ids[first + i] * B;
+      uint8_t *g = slot + (uint64_t)i * B;
+      if (s_hbm)
+        HIP_TRY(x, hipMemcpyAsync(h, g, (uint64_t)(j - i) * B, hipMemcpyDeviceToHost, d.side));
+      else
+        HIP_TRY(x, hipMemcpyAsync(g, h, (uint64_t)(j - i) * B, hipMemcpyHostToDevice, d.side));
+      i = j;
+    }
+    if (s_hbm) {
+      HIP_TRY(x, hipEventRecord(d.slot_drained[s], d.side));
+    } else {
+      HIP_TRY(x, hipEventRecord(d.slot_filled[s], d.side));
+      HIP_TRY(x, hipStreamWaitEvent(d.stream, d.slot_filled[s], 0));
+      {
+        ProfScope ps(x, kProfScatter, 2ull * cnt * B);
+        HIP_TRY(x, launch_block_copy(record_side(x, slot), pool_side(dst, d_dst + first), cnt,
+                                     x->P, x->F, tune, d.n_cus, d.stream));
+      }
+      HIP_TRY(x, hipEventRecord(d.slot_drained[s], d.stream));
+    }
+    d.slot_busy[s] = true;
+  }
+  if (s_hbm) {  // make the main stream the single point of completion
+    for (uint32_t s = 0; s < n_slots; ++s)
+      if (d.slot_busy[s]) HIP_TRY(x, hipStreamWaitEvent(d.stream, d.slot_drained[s], 0));
+  }
+  return MP_OK;
+}
+
+int finish_copy(mp_pool *src, mp_pool *dst, uint32_t flags) {
+  if (flags & MP_ASYNC) return MP_OK;
+  mp_pool *x = src->desc.tier == MP_TIER_HBM ? src : dst;
+  if (!x->dev.ready) return MP_OK;
+  HIP_TRY(x, hipStreamSynchronize(x->dev.stream));
+  return MP_OK;
+}
+
+// A transfer inside one pool with an explicit destination list may read and write the same
+// blocks.  The staged path is defined as "gather everything, then scatter", which holds only
+// if the whole table fits one staging round; the fused path cannot honour it at all.
+// (Freshly allocated destination ids never overlap held sources.)
+int check_same_pool(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *dst_ids,
+                    uint32_t n, uint32_t flags) {
+  if (src != dst || !(flags & MP_DST_GIVEN) || n == 0) return MP_OK;
+  if (!tables_overlap(src, src_ids, dst_ids, n)) return MP_OK;
+  if (flags & MP_DIRECT)
+    return fail(src, MP_EINVAL, "MP_DIRECT within one pool needs disjoint tables");
+  if ((uint64_t)n * src->B > src->desc.staging_bytes)
+    return fail(src, MP_ENOSTAGING, "overlapping in-pool transfer must fit the staging buffer");
+  return MP_OK;
+}
+
+int check_src_ids(mp_pool *src, const int32_t *ids, uint32_t n) {
+  for (uint32_t i = 0; i < n; ++i)
+    if (!src->idx.in_range(ids[i]) || src->idx.is_free(ids[i]))
+      return fail(src, MP_EINVAL, "source block id out of range or free");
+  return MP_OK;
+}
+
+// host part of match on precomputed hashes
+void match_walk(mp_pool *p, const uint32_t *tokens, const uint64_t *hashes, uint32_t nblk,
+                int32_t *blocks_out, uint32_t *n_matched, uint32_t flags) {
+  p->idx.tick();
+  uint32_t m = p->idx.walk(tokens, hashes, nblk, blocks_out);
+  p->idx.touch(blocks_out, m);
+  if (flags & MP_MATCH_PIN)
+    for (uint32_t i = 0; i < m; ++i) p->idx.pin(blocks_out[i]);
+  *n_matched = m;
+}
+
+// Shared core of transfer_with_insert and its batched form.
+int twi_core(mp_pool *src, mp_pool *dst, const uint32_t *tokens, const uint32_t *tok_off,
+             uint32_t n_req, const uint32_t *first_block, const int32_t *src_blocks,
+             int32_t *dst_blocks, const uint32_t *blk_off, uint32_t flags, const void *priv,
+             uint64_t priv_len) {
+  if (!src || !dst) return MP_EINVAL;
+  if (!tok_off || !blk_off || (!first_block && n_req))
+    return fail(src, MP_EINVAL, "null offset / first_block array");
+  if (!same_geometry(src, dst)) return fail(src, MP_ESHAPE, "source and destination geometry differ");
+  if (blk_off[0] != 0 || tok_off[0] != 0) return fail(src, MP_EINVAL, "offsets must start at 0");
+  const uint32_t bs = dst->desc.block_size;
+  for (uint32_t r = 0; r < n_req; ++r) {
+    if (tok_off[r + 1] < tok_off[r] || blk_off[r + 1] < blk_off[r])
+      return fail(src, MP_EINVAL, "offsets must be non-decreasing");
+    const uint32_t nb = (tok_off[r + 1] - tok_off[r]) / bs, n = blk_off[r + 1] - blk_off[r];
+    if (first_block[r] > nb || (uint64_t)first_block[r] + n < nb)
+      return fail(src, MP_EINVAL, "first_block / table length inconsistent with the prompt");
+  }
+  const uint32_t total = blk_off[n_req];
+  if ((!src_blocks || !dst_blocks) && total) return fail(src, MP_EINVAL, "null block table");
+  if (!tokens && tok_off[n_req]) return fail(src, MP_EINVAL, "null tokens");
+  int rc = check_src_ids(src, src_blocks, total);
+  if (rc != MP_OK) return rc;
+  if ((flags & MP_DST_GIVEN) && !dst->idx.held_and_distinct(dst_blocks, total))
+    return fail(src, MP_EINVAL, "given destination ids must be held and distinct");
+  if ((rc = check_copy_feasible(src, dst, total, flags)) != MP_OK) return rc;
+  if ((rc = check_same_pool(src, dst, src_blocks, dst_blocks, total, flags)) != MP_OK) return rc;
+
+  // the receiver hashes the prompts (device kernel)
+  std::vector<uint32_t> hoff;
+  const uint32_t *htok = nullptr;
+  const uint64_t *hh = nullptr;
+  rc = device_hashes(dst, tokens, tok_off, n_req, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok,
+                     &hh);
+  if (rc != MP_OK) return rc;
+
+  // blocks [0, first_block) must already be indexed at the receiver
+  std::vector<std::vector<int32_t>> ids(n_req);
+  std::vector<uint32_t> present(n_req, 0);
+  for (uint32_t r = 0; r < n_req; ++r) {
+    const uint32_t nb = hoff[r + 1] - hoff[r], n = blk_off[r + 1] - blk_off[r];
+    ids[r].assign(std::max(nb, first_block[r] + n), kNoBlock);
+    present[r] = dst->idx.walk(htok + tok_off[r], hh + hoff[r], nb, ids[r].data());
+    if (present[r] < first_block[r])
+      return fail(src, MP_ESTALE, "claimed prefix is not in the destination index");
+  }
+  if (flags & MP_DST_GIVEN) {
+    if (n_req != 1) return fail(src, MP_EINVAL, "MP_DST_GIVEN is not supported in batched form");
+    for (uint32_t i = 0; i < total; ++i) ids[0][first_block[0] + i] = dst_blocks[i];
+    if (!dst->idx.adoptable(ids[0].data(), present[0], hoff[1]))
+      return fail(src, MP_EINVAL, "a given destination block is already indexed");
+  }
+  // allocation step, with the matched prefixes protected from on-demand eviction
+  for (uint32_t r = 0; r < n_req; ++r)
+    for (uint32_t i = 0; i < first_block[r]; ++i) dst->idx.pin(ids[r][i]);
+  auto unpin_all = [&]() {
+    for (uint32_t r = 0; r < n_req; ++r)
+      for (uint32_t i = 0; i < first_block[r]; ++i) dst->idx.unpin(ids[r][i]);
+  };
+  if (!(flags & MP_DST_GIVEN)) {
+    if (!dst->idx.alloc(total, dst_blocks, (flags & MP_EVICT_ON_DEMAND) != 0)) {
+      unpin_all();
+      return fail(src, MP_ENOMEM, "destination pool cannot supply the blocks");
+    }
+    for (uint32_t r = 0; r < n_req; ++r)
+      for (uint32_t i = 0; i < blk_off[r + 1] - blk_off[r]; ++i)
+        ids[r][first_block[r] + i] = dst_blocks[blk_off[r] + i];
+  }
+
+  // transmission step
+  rc = run_copy(src, dst, src_blocks, dst_blocks, total, flags);
+  if (rc == MP_OK) rc = finish_copy(src, dst, flags);
+  if (rc != MP_OK) {
+    unpin_all();
+    return rc;
+  }
+
+  // insertion step: only after all data is in place (or ordered behind it on the stream)
+  for (uint32_t r = 0; r < n_req; ++r)
+    dst->idx.insert(htok + tok_off[r], hh + hoff[r], hoff[r + 1] - hoff[r], ids[r].data());
+  unpin_all();
+  if (dst->cb) dst->cb(dst->cb_user, priv, priv_len, dst_blocks, total);
+  return MP_OK;
+}
+
+}  // namespace
+
+// =============================================================================================
+extern "C" {
+
+const char *mp_strerror(int code) {
+  switch (code) {
+    case MP_OK: return "ok";
+    case MP_EINVAL: return "invalid argument";
+    case MP_ESHAPE: return "geometry mismatch";
+    case MP_ENOMEM: return "out of blocks";
+    case MP_ENOSTAGING: return "staging buffer missing or too small";
+    case MP_EHIP: return "HIP runtime error";
+    case MP_ESTALE: return "claimed prefix not in destination index";
+    default: return "unknown error";
+  }
+}
+
+int mp_selftest(void) {
+  const uint32_t ds[] = {1, 2, 3, 5, 7, 8, 20, 64, 80, 160, 255, 256, 257, 1000, 4097, 65535,
+                         65536, 65537, 1u << 20, (1u << 20) + 1, 0x7fffffffu};
+  const uint32_t xs[] = {0, 1, 2, 63, 64, 65, 4095, 4096, 1u << 16, (1u << 24) - 1, 1u << 24,
+                         0x3fffffffu, 0x40000000u, 0x7ffffffeu, 0x7fffffffu};
+  for (uint32_t d : ds) {
+    const FastDiv f = make_fastdiv(d);
+    for (uint32_t x : xs)
+      for (uint32_t k = 0; k < 3; ++k) {
+        const uint32_t v = x >= k ? x - k : x;
+        if (fastdiv(v, f) != v / d) return MP_EINVAL;
+      }
+    for (uint64_t q = 0; q < 64; ++q) {  // around multiples of d
+      const uint64_t base = q * d * 33554431ull % 0x80000000ull / d * d;
+      for (int k = -1; k <= 1; ++k) {
+        const int64_t v = (int64_t)base + k;
+        if (v < 0 || v > 0x7fffffffll) continue;
+        if (fastdiv((uint32_t)v, f) != (uint32_t)v / d) return MP_EINVAL;
+      }
+    }
+  }
+  return MP_OK;
+}
+
+int mp_pool_create(const mp_pool_desc_t *desc, mp_pool_t **out) {
+  if (!desc || !out) return MP_EINVAL;
+  *out = nullptr;
+  if (!desc->n_layers || !desc->n_kv_heads || !desc->head_dim || !desc->block_size ||
+      !desc->elem_bytes || !desc->n_blocks || !desc->base)
+    return MP_EINVAL;
+  if (desc->tier != MP_TIER_HBM && desc->tier != MP_TIER_HOST_PINNED) return MP_EINVAL;
+  if (desc->n_blocks > 0x7fffffffu || desc->n_layers > 0x7fffu) return MP_EINVAL;
+  const uint64_t F = (uint64_t)desc->block_size * desc->n_kv_heads * desc->head_dim * desc->elem_bytes;
+  if (F % 16 != 0 || F > (1ull << 34)) return MP_EINVAL;
+  if (((uintptr_t)desc->base & 15u) || ((uintptr_t)desc->staging & 15u)) return MP_EINVAL;
+  mp_pool *p = new mp_pool;
+  p->desc = *desc;
+  p->F = F;
+  p->P = 2 * desc->n_layers;
+  p->B = F * p->P;
+  p->idx.init(desc->n_blocks, desc->block_size, desc->tier, desc->instance_id);
+  *out = p;
+  return MP_OK;
+}
+
+int mp_pool_destroy(mp_pool_t *p) {
+  if (!p) return MP_EINVAL;
+  DeviceCtx &d = p->dev;
+  if (d.ready) {
+    (void)hipStreamSynchronize(d.stream);
+    (void)hipStreamSynchronize(d.side);
+    prof_drain(p);
+    release(d.tables);
+    release(d.tokens);
+    release(d.offsets);
+    release(d.hashes);
+    (void)hipEventDestroy(d.tables_uploaded);
+    for (int s = 0; s < 2; ++s) {
+      (void)hipEventDestroy(d.slot_filled[s]);
+      (void)hipEventDestroy(d.slot_drained[s]);
+    }
+    (void)hipStreamDestroy(d.side);
+  }
+  delete p;
+  return MP_OK;
+}
+
+int mp_pool_stats(mp_pool_t *p, mp_pool_stats_t *out) {
+  if (!p || !out) return MP_EINVAL;
+  out->n_blocks = p->idx.n_blocks();
+  out->n_free = p->idx.n_free();
+  out->n_held = p->idx.n_held();
+  out->n_indexed = p->idx.n_indexed();
+  out->n_historical = p->idx.n_historical();
+  out->clock = p->idx.clock();
+  return MP_OK;
+}
+
+const char *mp_last_error(mp_pool_t *p) { return p ? p->err.c_str() : "null pool"; }
+
+int mp_alloc(mp_pool_t *p, uint32_t n, int32_t *blocks_out, uint32_t flags) {
+  if (!p) return MP_EINVAL;
+  if (!blocks_out && n) return fail(p, MP_EINVAL, "null output array");
+  if (!p->idx.alloc(n, blocks_out, (flags & MP_EVICT_ON_DEMAND) != 0))
+    return fail(p, MP_ENOMEM, "not enough free (or evictable) blocks");
+  return MP_OK;
+}
+
+int mp_free(mp_pool_t *p, const int32_t *blocks, uint32_t n) {
+  if (!p) return MP_EINVAL;
+  if (!blocks && n) return fail(p, MP_EINVAL, "null block list");
+  if (!p->idx.release(blocks, n)) return fail(p, MP_EINVAL, "id out of range or not referenced");
+  return MP_OK;
+}
+
+int mp_insert_hashed(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens,
+                     const uint64_t *hashes, const int32_t *blocks, uint32_t n_blocks,
+                     uint32_t flags, uint32_t *n_new_out) {
+  (void)flags;
+  if (!p) return MP_EINVAL;
+  if ((!tokens && n_tokens) || !n_new_out) return fail(p, MP_EINVAL, "null argument");
+  const uint32_t nb = n_tokens / p->desc.block_size;
+  if (n_blocks < nb || ((!blocks || !hashes) && nb))
+    return fail(p, MP_EINVAL, "fewer block ids than full blocks");
+  const uint32_t m = p->idx.walk(tokens, hashes, nb, nullptr);
+  if (!p->idx.adoptable(blocks, m, nb))
+    return fail(p, MP_EINVAL, "blocks to adopt must be held, un-indexed and distinct");
+  *n_new_out = p->idx.insert(tokens, hashes, nb, blocks);
+  return MP_OK;
+}
+
+int mp_match_hashed(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens,
+                    const uint64_t *hashes, int32_t *blocks_out, uint32_t cap,
+                    uint32_t *n_matched_out, uint32_t flags) {
+  if (!p) return MP_EINVAL;
+  if ((!tokens && n_tokens) || !n_matched_out || (!blocks_out && cap))
+    return fail(p, MP_EINVAL, "null argument");
+  uint32_t nb = std::min(n_tokens / p->desc.block_size, cap);
+  if (!hashes && nb) return fail(p, MP_EINVAL, "null hashes");
+  match_walk(p, tokens, hashes, nb, blocks_out, n_matched_out, flags);
+  return MP_OK;
+}
+
+int mp_block_hashes(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, uint64_t *out,
+                    uint32_t flags) {
+  if (!p) return MP_EINVAL;
+  if ((!tokens && n_tokens) || (!out && n_tokens / p->desc.block_size))
+    return fail(p, MP_EINVAL, "null argument");
+  const uint32_t tok_off[2] = {0, n_tokens};
+  std::vector<uint32_t> hoff;
+  const uint32_t *htok;
+  const uint64_t *hh;
+  int rc = device_hashes(p, tokens, tok_off, 1, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok, &hh);
+  if (rc != MP_OK) return rc;
+  std::memcpy(out, hh, 8ull * hoff[1]);
+  return MP_OK;
+}
+
+int mp_insert(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, const int32_t *blocks,
+              uint32_t n_blocks, uint32_t flags, uint32_t *n_new_out) {
+  if (!p) return MP_EINVAL;
+  if ((!tokens && n_tokens) || !n_new_out) return fail(p, MP_EINVAL, "null argument");
+  const uint32_t nb = n_tokens / p->desc.block_size;
+  if (n_blocks < nb || (!blocks && nb)) return fail(p, MP_EINVAL, "fewer block ids than full blocks");
+  const uint32_t tok_off[2] = {0, n_tokens};
+  std::vector<uint32_t> hoff;
+  const uint32_t *htok;
+  const uint64_t *hh;
+  int rc = device_hashes(p, tokens, tok_off, 1, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok, &hh);
+  if (rc != MP_OK) return rc;
+  return mp_insert_hashed(p, htok, n_tokens, hh, blocks, n_blocks, flags, n_new_out);
+}
+
+int mp_match_batch(mp_pool_t *p, const uint32_t *tokens, const uint32_t *tok_off, uint32_t n_req,
+                   int32_t *blocks_out, const uint32_t *blk_off, uint32_t *n_matched_out,
+                   uint32_t flags) {
+  if (!p) return MP_EINVAL;
+  if (!tok_off || !blk_off || (!n_matched_out && n_req)) return fail(p, MP_EINVAL, "null argument");
+  if (tok_off[0] != 0) return fail(p, MP_EINVAL, "offsets must start at 0");
+  for (uint32_t r = 0; r < n_req; ++r)
+    if (tok_off[r + 1] < tok_off[r] || blk_off[r + 1] < blk_off[r])
+      return fail(p, MP_EINVAL, "offsets must be non-decreasing");
+  if (!tokens && tok_off[n_req]) return fail(p, MP_EINVAL, "null tokens");
+  if (!blocks_out && blk_off[n_req] != blk_off[0]) return fail(p, MP_EINVAL, "null output array");
+  std::vector<uint32_t> hoff;
+  const uint32_t *htok;
+  const uint64_t *hh;
+  int rc = device_hashes(p, tokens, tok_off, n_req, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok,
+                         &hh);
+  if (rc != MP_OK) return rc;
+  for (uint32_t r = 0; r < n_req; ++r) {
+    const uint32_t nb = std::min(hoff[r + 1] - hoff[r], blk_off[r + 1] - blk_off[r]);
+    match_walk(p, htok + tok_off[r], hh + hoff[r], nb, blocks_out + blk_off[r], &n_matched_out[r],
+               flags);
+  }
+  return MP_OK;
+}
+
+int mp_match(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, int32_t *blocks_out,
+             uint32_t cap, uint32_t *n_matched_out, uint32_t flags) {
+  if (!p) return MP_EINVAL;
+  if (!n_matched_out) return fail(p, MP_EINVAL, "null argument");
+  const uint32_t tok_off[2] = {0, n_tokens}, blk_off[2] = {0, cap};
+  return mp_match_batch(p, tokens, tok_off, 1, blocks_out, blk_off, n_matched_out, flags);
+}
+
+int mp_evict(mp_pool_t *p, uint32_t n_blocks, uint32_t *n_evicted_out) {
+  if (!p) return MP_EINVAL;
+  if (!n_evicted_out) return fail(p, MP_EINVAL, "null argument");
+  *n_evicted_out = p->idx.evict(n_blocks);
+  return MP_OK;
+}
+
+int mp_transfer(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks, int32_t *dst_blocks,
+                uint32_t n, uint32_t flags, const void *priv, uint64_t priv_len) {
+  if (!src || !dst) return MP_EINVAL;
+  if ((!src_blocks || !dst_blocks) && n) return fail(src, MP_EINVAL, "null block table");
+  if (!same_geometry(src, dst)) return fail(src, MP_ESHAPE, "source and destination geometry differ");
+  int rc = check_src_ids(src, src_blocks, n);
+  if (rc != MP_OK) return rc;
+  if ((flags & MP_DST_GIVEN) && !dst->idx.held_and_distinct(dst_blocks, n))
+    return fail(src, MP_EINVAL, "given destination ids must be held and distinct");
+  if ((rc = check_copy_feasible(src, dst, n, flags)) != MP_OK) return rc;
+  if ((rc = check_same_pool(src, dst, src_blocks, dst_blocks, n, flags)) != MP_OK) return rc;
+  if (!(flags & MP_DST_GIVEN) &&
+      !dst->idx.alloc(n, dst_blocks, (flags & MP_EVICT_ON_DEMAND) != 0))
+    return fail(src, MP_ENOMEM, "destination pool cannot supply the blocks");
+  rc = run_copy(src, dst, src_blocks, dst_blocks, n, flags);
+  if (rc == MP_OK) rc = finish_copy(src, dst, flags);
+  if (rc != MP_OK) return rc;
+  if (dst->cb) dst->cb(dst->cb_user, priv, priv_len, dst_blocks, n);
+  return MP_OK;
+}
+
+int mp_transfer_with_insert(mp_pool_t *src, mp_pool_t *dst, const uint32_t *tokens,
+                            uint32_t n_tokens, uint32_t first_block, const int32_t *src_blocks,
+                            int32_t *dst_blocks, uint32_t n, uint32_t flags, const void *priv,
+                            uint64_t priv_len) {
+  const uint32_t tok_off[2] = {0, n_tokens}, blk_off[2] = {0, n};
+  return twi_core(src, dst, tokens, tok_off, 1, &first_block, src_blocks, dst_blocks, blk_off,
+                  flags, priv, priv_len);
+}
+
+int mp_transfer_with_insert_batch(mp_pool_t *src, mp_pool_t *dst, const uint32_t *tokens,
+                                  const uint32_t *tok_off, uint32_t n_req,
+                                  const uint32_t *first_block, const int32_t *src_blocks,
+                                  int32_t *dst_blocks, const uint32_t *blk_off, uint32_t flags) {
+  if (src && (flags & MP_DST_GIVEN))
+    return fail(src, MP_EINVAL, "MP_DST_GIVEN is not supported in batched form");
+  return twi_core(src, dst, tokens, tok_off, n_req, first_block, src_blocks, dst_blocks, blk_off,
+                  flags, nullptr, 0);
+}
+
+int mp_gather(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags) {
+  if (!p) return MP_EINVAL;
+  if (!tbl && n) return fail(p, MP_EINVAL, "null table");
+  if (p->desc.tier != MP_TIER_HBM) return fail(p, MP_EINVAL, "mp_gather needs an HBM pool");
+  for (uint32_t i = 0; i < n; ++i)
+    if (!p->idx.in_range(tbl[i])) return fail(p, MP_EINVAL, "block id out of range");
+  if (n == 0) return MP_OK;
+  if (!p->desc.staging || (uint64_t)n * p->B > p->desc.staging_bytes)
+    return fail(p, MP_ENOSTAGING, "staging buffer too small for the table");
+  int rc = ensure_device(p);
+  if (rc != MP_OK) return rc;
+  const int32_t *d_src, *d_dst;
+  if ((rc = upload_tables(p, tbl, nullptr, n, &d_src, &d_dst)) != MP_OK) return rc;
+  {
+    ProfScope ps(p, kProfGather, 2ull * n * p->B);
+    HIP_TRY(p, launch_block_copy(pool_side(p, d_src), record_side(p, p->desc.staging), n, p->P,
+                                 p->F, effective_tune(p), p->dev.n_cus, p->dev.stream));
+  }
+  if (!(flags & MP_ASYNC)) HIP_TRY(p, hipStreamSynchronize(p->dev.stream));
+  return MP_OK;
+}
+
+int mp_scatter(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags) {
+  if (!p) return MP_EINVAL;
+  if (!tbl && n) return fail(p, MP_EINVAL, "null table");
+  if (p->desc.tier != MP_TIER_HBM) return fail(p, MP_EINVAL, "mp_scatter needs an HBM pool");
+  std::vector<uint8_t> seen(p->desc.n_blocks, 0);
+  for (uint32_t i = 0; i < n; ++i) {
+    if (!p->idx.in_range(tbl[i]) || seen[tbl[i]])
+      return fail(p, MP_EINVAL, "block id out of range or repeated");
+    seen[tbl[i]] = 1;
+  }
+  if (n == 0) return MP_OK;
+  if (!p->desc.staging || (uint64_t)n * p->B > p->desc.staging_bytes)
+    return fail(p, MP_ENOSTAGING, "staging buffer too small for the table");
+  int rc = ensure_device(p);
+  if (rc != MP_OK) return rc;
+  const int32_t *d_src, *d_dst;
+  if ((rc = upload_tables(p, nullptr, tbl, n, &d_src, &d_dst)) != MP_OK) return rc;
+  {
+    ProfScope ps(p, kProfScatter, 2ull * n * p->B);
+    HIP_TRY(p, launch_block_copy(record_side(p, p->desc.staging), pool_side(p, d_dst), n, p->P,
+                                 p->F, effective_tune(p), p->dev.n_cus, p->dev.stream));
+  }
+  if (!(flags & MP_ASYNC)) HIP_TRY(p, hipStreamSynchronize(p->dev.stream));
+  return MP_OK;
+}
+
+int mp_set_recv_callback(mp_pool_t *p, mp_recv_cb cb, void *user) {
+  if (!p) return MP_EINVAL;
+  p->cb = cb;
+  p->cb_user = user;
+  return MP_OK;
+}
+
+int mp_profile_enable(mp_pool_t *p, int on) {
+  if (!p) return MP_EINVAL;
+  p->dev.profiling = on != 0;
+  return MP_OK;
+}
+
+int mp_profile_read(mp_pool_t *p, int kind, double *total_ms_out, uint64_t *launches_out,
+                    uint64_t *bytes_out) {
+  if (!p) return MP_EINVAL;
+  if (kind < 0 || kind >= kProfKinds) return fail(p, MP_EINVAL, "unknown kernel kind");
+  prof_drain(p);
+  if (total_ms_out) *total_ms_out = p->dev.prof_ms[kind];
+  if (launches_out) *launches_out = p->dev.prof_launches[kind];
+  if (bytes_out) *bytes_out = p->dev.prof_bytes[kind];
+  p->dev.prof_ms[kind] = 0;
+  p->dev.prof_launches[kind] = 0;
+  p->dev.prof_bytes[kind] = 0;
+  return MP_OK;
+}
+
+int mp_set_tunable(mp_pool_t *p, const char *key, int value) {
+  if (!p || !key) return MP_EINVAL;
+  const std::string k(key);
+  if (k == "order" && (value == 0 || value == 1)) p->tune.order = value;
+  else if (k == "unroll" && (value == 1 || value == 2 || value == 4 || value == 8)) p->tune.unroll = value;
+  else if (k == "wg_per_cu" && value >= 0 && value <= 64) p->tune.wg_per_cu = value;
+  else if (k == "nontemporal" && (value == 0 || value == 1)) p->tune.nontemporal = value;
+  else return fail(p, MP_EINVAL, "unknown tunable or value out of range");
+  return MP_OK;
+}
+
+}  // extern "C"

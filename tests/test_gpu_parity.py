@@ -1,0 +1,443 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle -- bit-exact,
+because the work is byte copies and integer hashes.  Sizes span several wave-items, several
+staging rounds and ragged tails; the full-size configurations are in test_gpu_fullsize.py."""
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_2406_17565_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: -m gpu tests need a real MI355X")
+    from paper_2406_17565_amd import mempool as M
+    from paper_2406_17565_amd.pool import TorchPool
+    return M, TorchPool
+
+
+GEOMS = {  # name: (L, H, D, bs, e)
+    "tiny": (2, 2, 64, 16, 2),          # F = 4 KiB
+    "f64": (3, 1, 8, 4, 2),             # F = 64 B: a fragment smaller than one wave-load
+    "f480": (1, 5, 24, 2, 2),           # F = 480 B: multiple of 16, not of 64 -> ragged lanes
+    "f32k": (4, 8, 128, 16, 2),         # F = 32 KiB (config 3's fragment), several chunks
+    "f2560": (2, 5, 128, 2, 1),         # F = 1280 B with 1-byte elements
+    "f20k": (3, 5, 128, 16, 1),         # F = 10 KiB: 2.5 wave-items at unroll 4
+}
+
+
+def make_pair(gpu, geom, NB, seed, staging_blocks, tier=0, hash_seed=0):
+    M, TorchPool = gpu
+    L, H, D, bs, e = geom
+    rng = np.random.default_rng(seed)
+    data = W.kv_bytes(rng, 2 * L * NB * bs * H * D * e)
+    o = O.OraclePool(*geom, NB, tier=tier, seed=hash_seed, data=data.copy())
+    g = TorchPool(*geom, NB, tier=tier, staging_blocks=staging_blocks, seed=hash_seed)
+    g.load(data)
+    return o, g
+
+
+# ---- a1: chained block hash ------------------------------------------------------------------
+@pytest.mark.parametrize("bs", [16, 32, 4])
+def test_block_hashes(gpu, bs):
+    M, TorchPool = gpu
+    geom = (1, 1, 8, bs, 2)
+    rng = np.random.default_rng(bs)
+    for seed in (0, 0x1234567890ABCDEF):
+        p = TorchPool(*geom, 4, seed=seed)
+        for n in [0, 1, bs - 1, bs, bs + 1, 3 * bs, 64 * bs, 65 * bs + 3, 1024 * bs, 1025 * bs + 1,
+                  2500 * bs + 7]:
+            t = rng.integers(0, 2**32, n, dtype=np.uint32)
+            rc, h = M.mp_block_hashes(p.h, t, bs)
+            assert rc == 0, M.mp_last_error(p.h)
+            assert np.array_equal(h, O.block_hashes(t, bs, seed)), (bs, n)
+            dt = torch.from_numpy(t.view(np.int32)).cuda()
+            rc, h2 = M.mp_block_hashes(p.h, dt.data_ptr() if n else 0, bs, M.MP_TOKENS_ON_DEVICE,
+                                       n_tokens=n)
+            assert rc == 0 and np.array_equal(h2, h)
+        p.close()
+
+
+def test_block_hashes_golden(gpu, golden_dir):
+    M, TorchPool = gpu
+    import os
+    cases = {"arange48": np.arange(48), "zeros32": np.zeros(32), "arange64": np.arange(64),
+             "arange16": np.arange(16)}
+    for line in open(os.path.join(golden_dir, "block_hash_vectors.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        case, bs, seed, i, d, h = line.split()
+        p = TorchPool(1, 1, 8, int(bs), 2, 4, seed=int(seed))
+        rc, got = M.mp_block_hashes(p.h, cases[case].astype(np.uint32), int(bs))
+        assert rc == 0 and int(got[int(i)]) == int(h, 16)
+        p.close()
+
+
+# ---- a5 / a6: gather and scatter ----------------------------------------------------------------
+@pytest.mark.parametrize("name", list(GEOMS))
+def test_gather_scatter_all_launch_shapes(gpu, name):
+    M, TorchPool = gpu
+    geom = GEOMS[name]
+    NB, n = 61, 45
+    o, g = make_pair(gpu, geom, NB, 1, staging_blocks=n)
+    rng = np.random.default_rng(2)
+    src_tbl = rng.integers(0, NB, n).astype(np.int32)      # duplicates allowed when reading
+    dst_tbl = W.random_table(rng, NB, n)
+    want_staging = o.gather(src_tbl)
+    shapes = [(order, u, wg, nt) for order in (0, 1) for u in (1, 2, 4, 8)
+              for wg, nt in ((0, 1), (2, 0))]
+    for order, u, wg, nt in shapes:
+        for k, v in (("order", order), ("unroll", u), ("wg_per_cu", wg), ("nontemporal", nt)):
+            assert M.mp_set_tunable(g.h, k, v) == 0
+        g.staging.zero_()
+        assert M.mp_gather(g.h, src_tbl) == 0, M.mp_last_error(g.h)
+        assert np.array_equal(g.staging_bytes(n), want_staging), (name, order, u, wg, nt)
+        # scatter the gathered records under a permuted table; oracle does the same
+        o2 = O.OraclePool(*geom, NB, data=o.data.copy())
+        o2.scatter(dst_tbl, want_staging)
+        before = g.bytes()
+        assert M.mp_scatter(g.h, dst_tbl) == 0
+        assert np.array_equal(g.bytes(), o2.data), (name, order, u, wg, nt)
+        g.load(before)
+    assert M.mp_gather(g.h, np.zeros(0, np.int32)) == 0
+    assert M.mp_gather(g.h, [NB]) == M.MP_EINVAL
+    assert M.mp_scatter(g.h, [1, 1]) == M.MP_EINVAL
+    assert M.mp_gather(g.h, np.zeros(n + 1, np.int32)) == M.MP_ENOSTAGING
+    g.close()
+
+
+def test_special_bit_patterns_survive(gpu):
+    M, TorchPool = gpu
+    geom = GEOMS["tiny"]
+    o, g = make_pair(gpu, geom, 8, 3, staging_blocks=8)
+    o.data.reshape(geom[0], 2, 8, o.F)[:, :, 5, :] = W.special_half_patterns(o.F)
+    g.load(o.data)
+    tbl = np.array([5, 0, 5], np.int32)
+    assert M.mp_gather(g.h, tbl) == 0
+    assert np.array_equal(g.staging_bytes(3), o.gather(tbl))
+    g.close()
+
+
+# ---- the whole transfer workflow -----------------------------------------------------------------
+def _same_state(o, g):
+    assert np.array_equal(g.bytes(), o.data)
+    assert g.stats() == o.stats()
+
+
+@pytest.mark.parametrize("mode", ["staged", "rounds", "direct"])
+def test_transfer_and_errors(gpu, mode):
+    M, TorchPool = gpu
+    geom = GEOMS["f480"]
+    flags = M.MP_DIRECT if mode == "direct" else 0
+    so, sg = make_pair(gpu, geom, 40, 4, staging_blocks=3 if mode == "rounds" else 40)
+    do, dg = make_pair(gpu, geom, 30, 5, staging_blocks=0)
+    assert M.mp_alloc(sg.h, 40)[0] == so.alloc(40)[0] == 0
+    rng = np.random.default_rng(6)
+    tbl = rng.integers(0, 40, 17).astype(np.int32)
+    rc, d = M.mp_transfer(sg.h, dg.h, tbl, flags=flags)
+    rco, d_o = O.transfer(so, do, tbl)
+    assert rc == rco == 0 and d.tolist() == d_o.tolist()
+    _same_state(do, dg)
+    # explicit destination list (skips allocation)
+    given = d[::-1].copy()
+    rc, _ = M.mp_transfer(sg.h, dg.h, tbl, given, flags=flags | M.MP_DST_GIVEN)
+    rco, _ = O.transfer(so, do, tbl, given, flags=O.DST_GIVEN)
+    assert rc == rco == 0
+    _same_state(do, dg)
+    # errors leave everything untouched
+    snap = dg.bytes()
+    st = dg.stats()
+    for args, kw, want in [
+        (([40],), {}, M.MP_EINVAL),                                   # src id out of range
+        (([1, 2], [d[0], d[0]]), {"flags": M.MP_DST_GIVEN}, M.MP_EINVAL),   # duplicate dst
+        (([1, 2], [29, 28]), {"flags": M.MP_DST_GIVEN}, M.MP_EINVAL),       # dst not held
+        ((np.arange(14),), {}, M.MP_ENOMEM),                          # 13 free at dst
+    ]:
+        kw = dict(kw)
+        kw["flags"] = kw.get("flags", 0) | flags
+        rc, _ = M.mp_transfer(sg.h, dg.h, *args, **kw)
+        assert rc == want, (args, M.mp_last_error(sg.h))
+    other = TorchPool(3, 5, 24, 2, 2, 8)
+    assert M.mp_transfer(sg.h, other.h, [1])[0] == M.MP_ESHAPE
+    assert np.array_equal(dg.bytes(), snap) and dg.stats() == st
+    # n = 0
+    rc, d0 = M.mp_transfer(sg.h, dg.h, np.zeros(0, np.int32), flags=flags)
+    assert rc == 0 and d0.size == 0
+    for p in (sg, dg, other):
+        p.close()
+
+
+def test_transfer_without_staging_is_refused(gpu):
+    M, TorchPool = gpu
+    geom = GEOMS["f64"]
+    so, sg = make_pair(gpu, geom, 8, 1, staging_blocks=0)
+    do, dg = make_pair(gpu, geom, 8, 2, staging_blocks=0)
+    M.mp_alloc(sg.h, 8)
+    assert M.mp_transfer(sg.h, dg.h, [1, 2])[0] == M.MP_ENOSTAGING
+    assert dg.stats()["n_free"] == 8
+    rc, d = M.mp_transfer(sg.h, dg.h, [1, 2], flags=M.MP_DIRECT)   # the fused path needs none
+    assert rc == 0 and d.tolist() == [0, 1]
+    sg.close()
+    dg.close()
+
+
+def test_transfer_inside_one_pool(gpu):
+    M, TorchPool = gpu
+    geom = GEOMS["f64"]
+    o, g = make_pair(gpu, geom, 12, 7, staging_blocks=3)
+    M.mp_alloc(g.h, 6)
+    o.alloc(6)
+    rc, _ = M.mp_transfer(g.h, g.h, [0, 1, 2], [1, 2, 0], flags=M.MP_DST_GIVEN)   # rotation, one round
+    rco, _ = O.transfer(o, o, [0, 1, 2], [1, 2, 0], flags=O.DST_GIVEN)
+    assert rc == rco == 0
+    _same_state(o, g)
+    # overlapping tables that need two rounds, or the fused kernel: refused
+    assert M.mp_transfer(g.h, g.h, [0, 1, 2, 3], [1, 2, 3, 0], flags=M.MP_DST_GIVEN)[0] == M.MP_ENOSTAGING
+    assert M.mp_transfer(g.h, g.h, [0, 1], [1, 0], flags=M.MP_DST_GIVEN | M.MP_DIRECT)[0] == M.MP_EINVAL
+    # fresh destination ids cannot overlap: rounds and fused are fine
+    for fl in (0, M.MP_DIRECT):
+        rc, d = M.mp_transfer(g.h, g.h, [0, 1, 2, 3], flags=fl)
+        rco, d_o = O.transfer(o, o, [0, 1, 2, 3])
+        assert rc == rco == 0 and d.tolist() == d_o.tolist()
+        M.mp_free(g.h, d)
+        o.free(d_o)
+        _same_state(o, g)
+    g.close()
+
+
+def test_tiny_config_walkthrough(gpu):
+    """Config 1: match, transfer_with_insert of the unmatched suffix, match again."""
+    M, TorchPool = gpu
+    g_ = W.CONFIGS[1]
+    geom = (g_.L, g_.H, g_.D, g_.bs, g_.e)
+    so, sg = make_pair(gpu, geom, g_.NB, 1, staging_blocks=8)
+    do = O.OraclePool(*geom, g_.NB)
+    dg = TorchPool(*geom, g_.NB)
+    dg.mem.zero_()
+    M.mp_alloc(sg.h, g_.NB)
+    so.alloc(g_.NB)
+    rng = np.random.default_rng(1)
+    moved = []
+    for t in W.tiny_requests():
+        tbl = W.random_table(rng, g_.NB, 8)
+        rc, m = M.mp_match(dg.h, t, 8, M.MP_MATCH_PIN)
+        rco, mo = do.match(t, flags=O.MATCH_PIN)
+        assert rc == rco == 0 and m.tolist() == mo.tolist()
+        rc, d = M.mp_transfer_with_insert(sg.h, dg.h, t, len(m), tbl[len(m):])
+        rco, d_o = O.transfer_with_insert(so, do, t, len(mo), tbl[len(mo):])
+        assert rc == rco == 0 and d.tolist() == d_o.tolist(), M.mp_last_error(sg.h)
+        moved.append(len(d))
+        assert M.mp_match(dg.h, t, 8)[1].tolist() == do.match(t)[1].tolist() == m.tolist() + d.tolist()
+        _same_state(do, dg)
+    assert moved == [8, 4, 4, 4, 4, 4, 4, 4]
+    sg.close()
+    dg.close()
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_random_workflow_against_oracle(gpu, seed):
+    """Random interleaving of match / transfer_with_insert / free / evict on a small, tight
+    destination pool: ids, index answers, statistics and every pool byte must agree."""
+    M, TorchPool = gpu
+    geom = GEOMS["f64"]
+    bs = geom[3]
+    rng = np.random.default_rng(100 + seed)
+    so, sg = make_pair(gpu, geom, 64, seed, staging_blocks=5)
+    do, dg = make_pair(gpu, geom, 24, seed + 50, staging_blocks=0, hash_seed=seed)
+    M.mp_alloc(sg.h, 64)
+    so.alloc(64)
+    prompts, live = [], []
+    for step in range(60):
+        if prompts and rng.integers(0, 2):
+            base = prompts[int(rng.integers(0, len(prompts)))]
+            t = np.concatenate([base, rng.integers(0, 50, int(rng.integers(1, 3 * bs)), dtype=np.uint32)])
+        else:
+            t = rng.integers(0, 50, int(rng.integers(0, 6 * bs)), dtype=np.uint32)
+        nblk = (len(t) + bs - 1) // bs
+        rc, m = M.mp_match(dg.h, t, nblk, M.MP_MATCH_PIN)
+        rco, mo = do.match(t, flags=O.MATCH_PIN)
+        assert rc == rco == 0 and m.tolist() == mo.tolist()
+        tbl = rng.integers(0, 64, nblk - len(m)).astype(np.int32)
+        fl = M.MP_EVICT_ON_DEMAND if rng.integers(0, 3) else 0
+        if rng.integers(0, 4) == 0:
+            fl |= M.MP_DIRECT
+        rc, d = M.mp_transfer_with_insert(sg.h, dg.h, t, len(m), tbl, flags=fl)
+        rco, d_o = O.transfer_with_insert(so, do, t, len(mo), tbl, flags=fl & 0x3)
+        assert rc == rco, (step, rc, rco, M.mp_last_error(sg.h))
+        if rc == 0:
+            assert d.tolist() == d_o.tolist()
+            prompts.append(t)
+            live.append(np.concatenate([m, d]))
+        else:
+            live.append(m)
+        if len(live) > 3 or rc != 0:      # requests finish: their blocks become historical
+            k = int(rng.integers(0, len(live)))
+            ids = live.pop(k)
+            assert M.mp_free(dg.h, ids) == do.free(ids) == 0
+        if rng.integers(0, 5) == 0:
+            k = int(rng.integers(0, 4))
+            assert M.mp_evict(dg.h, k) == do.evict(k)
+        _same_state(do, dg)
+    sg.close()
+    dg.close()
+
+
+def test_stale_prefix_and_given_destinations(gpu):
+    M, TorchPool = gpu
+    geom = GEOMS["f64"]
+    bs = geom[3]
+    so, sg = make_pair(gpu, geom, 32, 1, staging_blocks=8)
+    do, dg = make_pair(gpu, geom, 16, 2, staging_blocks=0)
+    M.mp_alloc(sg.h, 32)
+    so.alloc(32)
+    rng = np.random.default_rng(9)
+    t1 = rng.integers(0, 1000, 3 * bs, dtype=np.uint32)
+    t2 = np.concatenate([t1, rng.integers(0, 1000, 2 * bs + 1, dtype=np.uint32)])
+    assert M.mp_transfer_with_insert(sg.h, dg.h, t1, 0, [10, 11, 12])[0] == 0
+    O.transfer_with_insert(so, do, t1, 0, [10, 11, 12])
+    snap, st = dg.bytes(), dg.stats()
+    assert M.mp_transfer_with_insert(sg.h, dg.h, t2, 4, [20, 21])[0] == M.MP_ESTALE
+    assert M.mp_transfer_with_insert(sg.h, dg.h, t2, 3, [20])[0] == M.MP_EINVAL
+    assert M.mp_transfer_with_insert(sg.h, dg.h, t2, 6, [])[0] == M.MP_EINVAL
+    assert np.array_equal(dg.bytes(), snap) and dg.stats() == st
+    # explicit destinations: allocate first, then transfer_with_insert into them
+    rc, mine = M.mp_alloc(dg.h, 3)
+    rco, mine_o = do.alloc(3)
+    rc, d = M.mp_transfer_with_insert(sg.h, dg.h, t2, 3, [20, 21, 22], mine, flags=M.MP_DST_GIVEN)
+    rco, d_o = O.transfer_with_insert(so, do, t2, 3, [20, 21, 22], mine_o, flags=O.DST_GIVEN)
+    assert rc == rco == 0 and d.tolist() == d_o.tolist() == mine.tolist()
+    _same_state(do, dg)
+    assert M.mp_match(dg.h, t2, 8)[1].tolist() == do.match(t2)[1].tolist()
+    # a given destination that is already indexed cannot be adopted again
+    t3 = rng.integers(0, 1000, bs, dtype=np.uint32)
+    assert M.mp_transfer_with_insert(sg.h, dg.h, t3, 0, [5], [mine[0]], flags=M.MP_DST_GIVEN)[0] == M.MP_EINVAL
+    assert O.transfer_with_insert(so, do, t3, 0, [5], [mine_o[0]], flags=O.DST_GIVEN)[0] == O.EINVAL
+    _same_state(do, dg)
+    sg.close()
+    dg.close()
+
+
+def test_batched_forms(gpu):
+    M, TorchPool = gpu
+    geom = GEOMS["tiny"]
+    bs = geom[3]
+    rng = np.random.default_rng(12)
+    so, sg = make_pair(gpu, geom, 96, 3, staging_blocks=7)       # several staging rounds
+    do, dg = make_pair(gpu, geom, 200, 4, staging_blocks=0)
+    M.mp_alloc(sg.h, 96)
+    so.alloc(96)
+    shared = rng.integers(0, 32000, 3 * bs, dtype=np.uint32)
+    for turn in range(3):
+        prompts = [np.concatenate([shared, rng.integers(0, 32000, int(n), dtype=np.uint32)])
+                   for n in rng.integers(0, 5 * bs, 6)] + [np.zeros(0, np.uint32)]
+        toks, tok_off = W.csr(prompts)
+        nblk = np.array([(len(p) + bs - 1) // bs for p in prompts], np.uint32)
+        cap_off = np.concatenate([[0], np.cumsum(nblk)]).astype(np.uint32)
+        rc, mb, m = M.mp_match_batch(dg.h, toks, tok_off, cap_off, M.MP_MATCH_PIN)
+        assert rc == 0
+        mo = [do.match(p, flags=O.MATCH_PIN)[1] for p in prompts]
+        assert m.tolist() == [len(x) for x in mo]
+        for r in range(len(prompts)):
+            assert mb[cap_off[r]:cap_off[r] + m[r]].tolist() == mo[r].tolist()
+        tables = [rng.integers(0, 96, int(nblk[r] - m[r])).astype(np.int32) for r in range(len(prompts))]
+        s, blk_off = W.csr(tables, np.int32)
+        rc, d = M.mp_transfer_with_insert_batch(sg.h, dg.h, toks, tok_off, m, s, blk_off)
+        rco, d_o = O.transfer_with_insert_batch(so, do, toks, tok_off, m, s, blk_off)
+        assert rc == rco == 0 and d.tolist() == d_o.tolist(), M.mp_last_error(sg.h)
+        _same_state(do, dg)
+        held = np.concatenate([mb[cap_off[r]:cap_off[r] + m[r]] for r in range(len(prompts))] + [d])
+        assert M.mp_free(dg.h, held) == do.free(held) == 0
+        _same_state(do, dg)
+    assert M.mp_transfer_with_insert_batch(sg.h, dg.h, toks, tok_off, m, s, blk_off,
+                                           flags=M.MP_DST_GIVEN)[0] == M.MP_EINVAL
+    sg.close()
+    dg.close()
+
+
+def test_host_tier_both_directions(gpu):
+    """HBM -> pinned host (swap-out / transfer to a DRAM tier) and back (swap-in)."""
+    M, TorchPool = gpu
+    geom = GEOMS["tiny"]
+    so, sg = make_pair(gpu, geom, 48, 1, staging_blocks=6)       # 2 slots of 3 records
+    ho, hg = make_pair(gpu, geom, 40, 2, staging_blocks=0, tier=1)
+    bo, bg = make_pair(gpu, geom, 48, 3, staging_blocks=4)
+    M.mp_alloc(sg.h, 48)
+    so.alloc(48)
+    rng = np.random.default_rng(5)
+    # fragment the host pool's free list so records do not land in one run
+    rc, a = M.mp_alloc(hg.h, 40)
+    ho.alloc(40)
+    perm = rng.permutation(40).astype(np.int32)
+    assert M.mp_free(hg.h, perm[:30]) == ho.free(perm[:30]) == 0
+    tbl = rng.integers(0, 48, 17).astype(np.int32)
+    rc, d = M.mp_transfer(sg.h, hg.h, tbl)
+    rco, d_o = O.transfer(so, ho, tbl)
+    assert rc == rco == 0 and d.tolist() == d_o.tolist(), M.mp_last_error(sg.h)
+    _same_state(ho, hg)
+    rc, d2 = M.mp_transfer(hg.h, bg.h, d)
+    rco, d2_o = O.transfer(ho, bo, d_o)
+    assert rc == rco == 0 and d2.tolist() == d2_o.tolist(), M.mp_last_error(hg.h)
+    _same_state(bo, bg)
+    # the round trip through the host tier is the identity on the moved blocks
+    assert M.mp_gather(bg.h, d2[:4]) == 0
+    assert np.array_equal(bg.staging_bytes(4), so.gather(tbl[:4]))
+    # transfer_with_insert into the host tier indexes DRAM-resident blocks
+    t = rng.integers(0, 32000, 3 * geom[3] + 1, dtype=np.uint32)
+    rc, d3 = M.mp_transfer_with_insert(sg.h, hg.h, t, 0, [3, 4, 5, 6])
+    rco, d3_o = O.transfer_with_insert(so, ho, t, 0, [3, 4, 5, 6])
+    assert rc == rco == 0 and d3.tolist() == d3_o.tolist()
+    _same_state(ho, hg)
+    assert M.mp_match(hg.h, t, 4)[1].tolist() == ho.match(t)[1].tolist()
+    assert M.mp_transfer(hg.h, hg.h, [int(d3[0])])[0] == M.MP_ESHAPE   # host -> host unsupported
+    for p in (sg, hg, bg):
+        p.close()
+
+
+def test_async_and_callback(gpu):
+    M, TorchPool = gpu
+    geom = GEOMS["f32k"]
+    so, sg = make_pair(gpu, geom, 24, 1, staging_blocks=24)
+    do, dg = make_pair(gpu, geom, 24, 2, staging_blocks=0)
+    M.mp_alloc(sg.h, 24)
+    so.alloc(24)
+    seen = []
+
+    def on_recv(user, priv, priv_len, blocks, n):
+        import ctypes
+        seen.append((ctypes.string_at(priv, priv_len) if priv else b"", [blocks[i] for i in range(n)]))
+
+    cb = M.RECV_CB(on_recv)
+    assert M.mp_set_recv_callback(dg.h, cb) == 0
+    tbl = np.arange(23, -1, -1, dtype=np.int32)
+    rc, d = M.mp_transfer(sg.h, dg.h, tbl, flags=M.MP_ASYNC, priv=b"req-42")
+    rc2, d2 = M.mp_transfer(sg.h, dg.h, tbl[:4], d[:4], flags=M.MP_ASYNC | M.MP_DST_GIVEN)
+    torch.cuda.synchronize()
+    O.transfer(so, do, tbl)
+    assert rc == rc2 == 0
+    _same_state(do, dg)
+    assert seen[0] == (b"req-42", d.tolist()) and seen[1][1] == d[:4].tolist()
+    M.mp_set_recv_callback(dg.h, None)
+    sg.close()
+    dg.close()
+
+
+def test_profile_counters(gpu):
+    M, TorchPool = gpu
+    geom = GEOMS["f32k"]
+    so, sg = make_pair(gpu, geom, 16, 1, staging_blocks=16)
+    do, dg = make_pair(gpu, geom, 16, 2, staging_blocks=0)
+    M.mp_alloc(sg.h, 16)
+    assert M.mp_profile_enable(sg.h, True) == 0
+    rc, d = M.mp_transfer(sg.h, dg.h, np.arange(16))
+    assert rc == 0
+    for kind in (M.PROF_GATHER, M.PROF_SCATTER):
+        rc, ms, n, nbytes = M.mp_profile_read(sg.h, kind)
+        assert rc == 0 and n == 1 and ms > 0 and nbytes == 2 * 16 * sg.B
+    assert M.mp_profile_read(sg.h, M.PROF_GATHER)[2] == 0      # cleared by the read
+    sg.close()
+    dg.close()
