@@ -63,22 +63,21 @@ __global__ __launch_bounds__(kThreads) void block_hash_kernel(
     // into scalar registers, so h lives in SGPRs and the multiplies issue on the scalar ALU.
     if (threadIdx.x < 64) {
       const uint32_t lane = threadIdx.x;
-      h = ((uint64_t)__builtin_amdgcn_readfirstlane((uint32_t)(h >> 32)) << 32) |
-          __builtin_amdgcn_readfirstlane((uint32_t)h);
+      // (the lane builtins return int: go through uint32_t so nothing gets sign-extended)
+      h = ((uint64_t)(uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)(h >> 32)) << 32) |
+          (uint32_t)__builtin_amdgcn_readfirstlane((uint32_t)h);
       for (uint32_t jj = 0; jj < cnt; jj += 64) {
         const uint64_t dv = (jj + lane < cnt) ? tile[jj + lane] : 0;
         const uint32_t dlo = (uint32_t)dv, dhi = (uint32_t)(dv >> 32);
-        uint64_t res = 0;
 #pragma unroll
         for (int k = 0; k < 64; ++k) {
           if (jj + k < cnt) {  // wave-uniform
-            const uint64_t d = ((uint64_t)__builtin_amdgcn_readlane(dhi, k) << 32) |
-                               __builtin_amdgcn_readlane(dlo, k);
+            const uint64_t d = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(dhi, k) << 32) |
+                               (uint32_t)__builtin_amdgcn_readlane(dlo, k);
             h = fmix64((h + kGolden) ^ d);
-            if (lane == (uint32_t)k) res = h;
+            if (lane == 0) tile[jj + k] = h;  // the digest of step k is already in registers
           }
         }
-        if (jj + lane < cnt) tile[jj + lane] = res;
       }
     }
     __syncthreads();
