@@ -1,0 +1,259 @@
+#!/usr/bin/env python3
+"""Benchmark of the KV-block transfer / match hot path on one MI355X.
+
+A "step" is one pass of the whole path over one batch: for the 64 sessions of a multi-turn
+workload (Llama-3-8B GQA-shaped KV, config 3), mp_match_batch against the destination index,
+then mp_transfer_with_insert_batch of every unmatched suffix (allocate, upload tables, gather,
+scatter, insert).  Four consecutive steps are the four turns of one set of sessions; after the
+fourth turn the sessions end (their blocks become historical) and a new set starts, so the
+destination pool evicts on demand in steady state.
+
+Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
+
+
+def build_epoch(W, geom, epoch, n_sessions, n_turns):
+    """Tokens of every turn of one set of sessions (fresh ids per epoch => no cross-epoch hits)."""
+    sessions = W.multiturn_sessions(seed=3 + 1000 * epoch, n_sessions=n_sessions, n_turns=n_turns,
+                                    vocab=geom.vocab)
+    turns = []
+    for t in range(n_turns):
+        prompts = [sessions[s][t] for s in range(n_sessions)]
+        toks, tok_off = W.csr(prompts)
+        nblk = np.array([(len(p) + geom.bs - 1) // geom.bs for p in prompts], dtype=np.uint32)
+        cap_off = np.concatenate([[0], np.cumsum(nblk)]).astype(np.uint32)
+        turns.append(dict(toks=toks, tok_off=tok_off, nblk=nblk, cap_off=cap_off))
+    return turns
+
+
+def run_step(M, src, dst, turn, rng, state, flags):
+    """One step.  Returns the number of blocks moved."""
+    rc, mb, m = M.mp_match_batch(dst.h, turn["toks"], turn["tok_off"], turn["cap_off"],
+                                 M.MP_MATCH_PIN)
+    assert rc == 0, M.mp_last_error(dst.h)
+    need = turn["nblk"] - m
+    blk_off = np.concatenate([[0], np.cumsum(need)]).astype(np.uint32)
+    total = int(blk_off[-1])
+    # the sender's KV sits in random (fragmented) blocks of its pool
+    src_blocks = rng.permutation(src.NB)[:total].astype(np.int32)
+    rc, d = M.mp_transfer_with_insert_batch(src.h, dst.h, turn["toks"], turn["tok_off"], m,
+                                            src_blocks, blk_off, flags)
+    assert rc == 0, M.mp_last_error(src.h)
+    pinned = [mb[turn["cap_off"][r]:turn["cap_off"][r] + m[r]] for r in range(len(m))]
+    state["held"].append(np.concatenate(pinned + [d]))
+    return total
+
+
+def cpu_baseline(W, geom, n_sessions=16, n_turns=4, NB_src=2048, NB_dst=4096):
+    """The CPU oracle on a bounded sample of the same workload: all turns of n_sessions sessions,
+    same geometry, reduced pool sizes; single thread."""
+    from oracle import oracle as O
+    rng = np.random.default_rng(3)
+    chunk = rng.integers(0, 256, 64 << 20, dtype=np.uint8)
+    src_data = np.tile(chunk, geom.pool_bytes(NB_src) // chunk.size)
+    src = O.OraclePool(geom.L, geom.H, geom.D, geom.bs, geom.e, NB_src, data=src_data)
+    dst = O.OraclePool(geom.L, geom.H, geom.D, geom.bs, geom.e, NB_dst)
+    src.alloc(NB_src)
+    turns = build_epoch(W, geom, 0, n_sessions, n_turns)
+    moved = hashed = 0
+    t_total = 0.0
+    for turn in turns:
+        tables = []
+        t0 = time.perf_counter()
+        ms = []
+        for r in range(n_sessions):
+            t = turn["toks"][turn["tok_off"][r]:turn["tok_off"][r + 1]]
+            ms.append(len(dst.match(t, flags=O.MATCH_PIN)[1]))
+        t_total += time.perf_counter() - t0
+        need = turn["nblk"] - np.array(ms, dtype=np.uint32)
+        blk_off = np.concatenate([[0], np.cumsum(need)]).astype(np.uint32)
+        src_blocks = rng.permutation(NB_src)[: int(blk_off[-1])].astype(np.int32)
+        t0 = time.perf_counter()
+        rc, d = O.transfer_with_insert_batch(src, dst, turn["toks"], turn["tok_off"], ms, src_blocks,
+                                             blk_off, flags=O.EVICT_ON_DEMAND)
+        t_total += time.perf_counter() - t0
+        assert rc == 0
+        moved += int(blk_off[-1])
+        hashed += int(sum(len(turn["toks"][turn["tok_off"][r]:turn["tok_off"][r + 1]]) // geom.bs
+                          for r in range(n_sessions)))
+    return dict(value=moved * geom.B / t_total / 1e9, unit="GB/s", cores=1, kind="oracle",
+                sample=f"config 3, all {n_turns} turns of {n_sessions} of the 64 sessions "
+                       f"({moved} blocks = {moved * geom.B / 2**30:.2f} GiB payload, {hashed} blocks "
+                       f"hashed+matched), pools reduced to {NB_src}/{NB_dst} blocks",
+                seconds=round(t_total, 3), blocks_per_s=round(moved / t_total, 1))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--config", type=int, default=3)
+    ap.add_argument("--direct", action="store_true", help="fused pool-to-pool kernel (no staging)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tune", default="", help="comma list key=value for mp_set_tunable")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run it with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2406_17565_amd import mempool as M
+    from paper_2406_17565_amd import workloads as W
+    from paper_2406_17565_amd.pool import TorchPool
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    geom = W.CONFIGS[args.config]
+    n_sessions, n_turns = 64, 4
+    L, H, D, bs, e = geom.L, geom.H, geom.D, geom.bs, geom.e
+
+    # staging holds one whole turn batch (<= 64 sessions * 49 blocks)
+    staging_blocks = n_sessions * ((512 + 256 + bs - 1) // bs + 2)
+    src = TorchPool(L, H, D, bs, e, geom.NB, staging_blocks=staging_blocks)
+    dst = TorchPool(L, H, D, bs, e, geom.NB)
+    # KV fill: N(0,1) in the model dtype, plane by plane (harness work, not the path)
+    torch.manual_seed(args.config)
+    tdt = torch.bfloat16 if geom.dtype == "bf16" else torch.float16
+    view = src.mem.view(tdt)
+    step_elems = 1 << 28
+    for off in range(0, view.numel(), step_elems):
+        n = min(step_elems, view.numel() - off)
+        view[off:off + n].normal_()
+    dst.mem.zero_()
+    torch.cuda.synchronize()
+    assert M.mp_alloc(src.h, geom.NB)[0] == 0      # the sender's engine owns all its blocks
+    for kv in filter(None, args.tune.split(",")):
+        k, v = kv.split("=")
+        for p in (src, dst):
+            assert M.mp_set_tunable(p.h, k, int(v)) == 0
+
+    flags = M.MP_EVICT_ON_DEMAND | (M.MP_DIRECT if args.direct else 0)
+    total_steps = args.warmup + args.steps
+    n_epochs = (total_steps + n_turns - 1) // n_turns
+    epochs = [build_epoch(W, geom, ep, n_sessions, n_turns) for ep in range(n_epochs)]
+    rng = np.random.default_rng(args.config)
+    state = dict(held=[])
+
+    def do_step(i):
+        ep, t = divmod(i, n_turns)
+        moved = run_step(M, src, dst, epochs[ep][t], rng, state, flags)
+        hashed = int(((epochs[ep][t]["tok_off"][1:] - epochs[ep][t]["tok_off"][:-1]) // bs).sum())
+        if t == n_turns - 1:       # the sessions end: everything they held becomes historical
+            for ids in state["held"]:
+                assert M.mp_free(dst.h, ids) == 0
+            state["held"].clear()
+        return moved, hashed
+
+    for i in range(args.warmup):
+        do_step(i)
+    torch.cuda.synchronize()
+    # yardstick: a plain contiguous device-to-device copy (pool -> staging) on the same box
+    cal_bytes = min(4 << 30, src.staging.numel() // 16 * 16)
+    cal_ms = []
+    for _ in range(4):
+        rc, ms = M.mp_plain_copy(src.staging.data_ptr(), src.mem.data_ptr(), cal_bytes,
+                                 src.stream.cuda_stream or None)
+        assert rc == 0
+        cal_ms.append(ms)
+    copy_ceiling = 2 * cal_bytes / (min(cal_ms[1:]) * 1e-3) / 1e9
+    M.mp_profile_enable(src.h, True)
+    M.mp_profile_enable(dst.h, True)
+    moved = hashed = 0
+    t0 = time.perf_counter()
+    for i in range(args.warmup, total_steps):
+        mv, hs = do_step(i)
+        moved += mv
+        hashed += hs
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    # the dominant kernel: the block-table copy (gather + scatter launches, or the fused one)
+    k_ms = k_n = k_bytes = 0
+    kinds = [M.PROF_DIRECT] if args.direct else [M.PROF_GATHER, M.PROF_SCATTER]
+    per_kind = {}
+    for kind in kinds:
+        rc, ms, n, nbytes = M.mp_profile_read(src.h, kind)
+        per_kind[kind] = (ms, n, nbytes)
+        k_ms, k_n, k_bytes = k_ms + ms, k_n + n, k_bytes + nbytes
+    _, h_ms, h_n, h_bytes = M.mp_profile_read(dst.h, M.PROF_HASH)
+    achieved = k_bytes / (k_ms * 1e-3) / 1e9 if k_ms else 0.0
+
+    # measured HBM traffic per algorithmic byte, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
+    # whose summary is committed under profiles/ (counters cannot be read from inside this run)
+    traffic = traffic_src = None
+    tpath = os.path.join(ROOT, "profiles", f"kv_block_copy_config{args.config}_"
+                         f"{'direct' if args.direct else 'staged'}_hbm_traffic.json")
+    if os.path.exists(tpath) and k_n:
+        with open(tpath) as f:
+            traffic = int(json.load(f)["traffic_per_algorithmic_byte"] * k_bytes / k_n)
+        traffic_src = os.path.relpath(tpath, ROOT)
+
+    payload = moved * geom.B
+    out = {
+        "metric": "KV transfer GB/s (gather+scatter) & % of HBM peak; match blocks/s, 1 MI355X",
+        "value": round(payload / dt / 1e9, 2),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(dt / args.steps * 1e3, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u8",
+        "data": "synthetic",
+        "config": {
+            "workload": f"config {args.config} ({geom.name}): {n_sessions} multi-turn sessions x "
+                        f"{n_turns} turns, match then transfer_with_insert of the unmatched suffix, "
+                        f"one batched call per turn",
+            "geometry": f"L={L} H={H} D={D} bs={bs} {geom.dtype}, F={geom.F} B={geom.B}, "
+                        f"pools {geom.NB} blocks ({geom.pool_bytes() / 2**30:.0f} GiB) each",
+            "path": "direct (fused pool->pool)" if args.direct else "staged (gather -> staging -> scatter)",
+            "blocks_moved": moved,
+            "payload_GiB": round(payload / 2**30, 3),
+        },
+        "match_blocks_per_s": round(hashed / dt, 1),
+        "hash_kernel": {"launches": h_n, "avg_us": round(h_ms / h_n * 1e3, 2) if h_n else None},
+        "roofline": {
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": traffic,
+            "traffic_source": traffic_src,
+            "plain_copy_ceiling_GBs": round(copy_ceiling, 1),
+            "frac_of_plain_copy": round(achieved / copy_ceiling, 4),
+            "kernel": "kv_block_copy",
+            "launches": k_n,
+            "avg_launch_us": round(k_ms / k_n * 1e3, 2) if k_n else None,
+            "alg_bytes_per_launch": int(k_bytes / k_n) if k_n else 0,
+            "per_kind_GBs": {("direct" if k == M.PROF_DIRECT else "gather" if k == M.PROF_GATHER
+                              else "scatter"): round(v[2] / (v[0] * 1e-3) / 1e9, 1) if v[0] else None
+                             for k, v in per_kind.items()},
+        },
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(W, geom)
+    print(json.dumps(out))
+    src.close()
+    dst.close()
+
+
+if __name__ == "__main__":
+    main()

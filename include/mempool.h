@@ -197,6 +197,12 @@ int mp_profile_read(mp_pool_t *p, int kind, double *total_ms_out, uint64_t *laun
  * "nontemporal" (0/1). */
 int mp_set_tunable(mp_pool_t *p, const char *key, int value);
 
+/* Calibration yardstick: one contiguous device-to-device copy of `bytes` (multiple of 16;
+ * dst, src: DEVICE pointers) with the same per-lane load/store shape as the table-driven
+ * copy, timed with HIP events on `stream`; synchronous.  Its time gives the copy ceiling of
+ * the GPU at hand; its hardware-counter readings scale those of the real kernels. */
+int mp_plain_copy(void *dst, const void *src, uint64_t bytes, void *stream, double *ms_out);
+
 /* Host-only self check of internal integer arithmetic (multiply-shift division used for
  * work-item decomposition).  Returns MP_OK or MP_EINVAL. */
 int mp_selftest(void);

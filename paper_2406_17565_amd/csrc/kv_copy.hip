@@ -83,6 +83,21 @@ __global__ __launch_bounds__(256) void kv_block_copy(const CopyArgs a,
   }
 }
 
+// Contiguous copy with the same per-lane shape (4 x 16-byte loads in flight, streaming
+// loads and stores): the yardstick for what a pure copy reaches on this GPU, and the kernel
+// whose hardware-counter readings calibrate the traffic figures of the table-driven copy.
+__global__ __launch_bounds__(256) void plain_copy_kernel(const u32x4 *__restrict__ src,
+                                                         u32x4 *__restrict__ dst, uint64_t n_vecs) {
+  const uint64_t base = (uint64_t)blockIdx.x * 1024u + threadIdx.x;
+  u32x4 reg[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (base + 256u * u < n_vecs) reg[u] = __builtin_nontemporal_load(src + base + 256u * u);
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (base + 256u * u < n_vecs) __builtin_nontemporal_store(reg[u], dst + base + 256u * u);
+}
+
 template <int U, int ORDER>
 hipError_t launch_nt(const CopyArgs &a, const int32_t *st, const int32_t *dt, bool nt, dim3 grid,
                      hipStream_t stream) {
@@ -101,6 +116,17 @@ hipError_t launch_order(const CopyArgs &a, const int32_t *st, const int32_t *dt,
 }
 
 }  // namespace
+
+hipError_t launch_plain_copy(void *dst, const void *src, uint64_t bytes, hipStream_t stream) {
+  if (bytes == 0) return hipSuccess;
+  if (!dst || !src || (bytes & 15u) || (bytes >> 4) > 0x7fffffffull * 1024ull)
+    return hipErrorInvalidValue;
+  const uint64_t n_vecs = bytes >> 4;
+  const uint64_t wgs = (n_vecs + 1023u) / 1024u;
+  hipLaunchKernelGGL(plain_copy_kernel, dim3((uint32_t)wgs), dim3(256), 0, stream,
+                     (const u32x4 *)src, (u32x4 *)dst, n_vecs);
+  return hipGetLastError();
+}
 
 hipError_t launch_block_copy(const CopySide &src, const CopySide &dst, uint32_t n,
                              uint32_t n_planes, uint64_t frag_bytes, const CopyTune &tune,

@@ -42,6 +42,9 @@ hipError_t launch_block_copy(const CopySide &src, const CopySide &dst, uint32_t 
                              uint32_t n_planes, uint64_t frag_bytes, const CopyTune &tune,
                              int n_cus, hipStream_t stream);
 
+// Contiguous device-to-device copy of `bytes` (a multiple of 16): the calibration yardstick.
+hipError_t launch_plain_copy(void *dst, const void *src, uint64_t bytes, hipStream_t stream);
+
 // Chained block hashes for a batch of prompts (one workgroup per prompt).
 //   tokens  : device, all prompts concatenated
 //   tok_off : device, n_req+1 token offsets

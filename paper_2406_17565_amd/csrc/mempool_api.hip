@@ -858,6 +858,27 @@ int mp_profile_read(mp_pool_t *p, int kind, double *total_ms_out, uint64_t *laun
   return MP_OK;
 }
 
+int mp_plain_copy(void *dst, const void *src, uint64_t bytes, void *stream, double *ms_out) {
+  if (!dst || !src || (bytes & 15u)) return MP_EINVAL;
+  hipStream_t s = (hipStream_t)stream;
+  hipEvent_t a, b;
+  if (hipEventCreate(&a) != hipSuccess) return MP_EHIP;
+  if (hipEventCreate(&b) != hipSuccess) {
+    (void)hipEventDestroy(a);
+    return MP_EHIP;
+  }
+  int rc = MP_OK;
+  float ms = 0.f;
+  if (hipEventRecord(a, s) != hipSuccess || launch_plain_copy(dst, src, bytes, s) != hipSuccess ||
+      hipEventRecord(b, s) != hipSuccess || hipEventSynchronize(b) != hipSuccess ||
+      hipEventElapsedTime(&ms, a, b) != hipSuccess)
+    rc = MP_EHIP;
+  (void)hipEventDestroy(a);
+  (void)hipEventDestroy(b);
+  if (ms_out) *ms_out = ms;
+  return rc;
+}
+
 int mp_set_tunable(mp_pool_t *p, const char *key, int value) {
   if (!p || !key) return MP_EINVAL;
   const std::string k(key);

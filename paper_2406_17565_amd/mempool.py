@@ -24,7 +24,7 @@ EXPORTS = [
     "mp_transfer_with_insert", "mp_match_batch", "mp_transfer_with_insert_batch",
     "mp_block_hashes", "mp_insert_hashed", "mp_match_hashed", "mp_gather", "mp_scatter",
     "mp_set_recv_callback", "mp_profile_enable", "mp_profile_read", "mp_set_tunable",
-    "mp_selftest",
+    "mp_selftest", "mp_plain_copy",
 ]
 
 
@@ -81,6 +81,7 @@ def lib():
             "mp_profile_read": [vp, i32, C.POINTER(C.c_double), C.POINTER(u64), C.POINTER(u64)],
             "mp_set_tunable": [vp, C.c_char_p, i32],
             "mp_selftest": [],
+            "mp_plain_copy": [vp, vp, u64, vp, C.POINTER(C.c_double)],
         }
         for name, args in sig.items():
             fn = getattr(L, name)
@@ -275,3 +276,9 @@ def mp_set_tunable(p, key, value):
 
 def mp_selftest():
     return lib().mp_selftest()
+
+
+def mp_plain_copy(dst_ptr, src_ptr, nbytes, stream=None):
+    ms = C.c_double(0)
+    rc = lib().mp_plain_copy(dst_ptr, src_ptr, nbytes, stream, C.byref(ms))
+    return rc, ms.value
