@@ -39,7 +39,7 @@ def build_epoch(W, geom, epoch, n_sessions, n_turns):
     return turns
 
 
-def run_step(M, src, dst, turn, rng, state, flags):
+def run_step(M, src, dst, turn, perm, state, flags):
     """One step.  Returns the number of blocks moved."""
     rc, mb, m = M.mp_match_batch(dst.h, turn["toks"], turn["tok_off"], turn["cap_off"],
                                  M.MP_MATCH_PIN)
@@ -48,7 +48,7 @@ def run_step(M, src, dst, turn, rng, state, flags):
     blk_off = np.concatenate([[0], np.cumsum(need)]).astype(np.uint32)
     total = int(blk_off[-1])
     # the sender's KV sits in random (fragmented) blocks of its pool
-    src_blocks = rng.permutation(src.NB)[:total].astype(np.int32)
+    src_blocks = perm[:total]
     rc, d = M.mp_transfer_with_insert_batch(src.h, dst.h, turn["toks"], turn["tok_off"], m,
                                             src_blocks, blk_off, flags)
     assert rc == 0, M.mp_last_error(src.h)
@@ -103,6 +103,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=4)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--direct", action="store_true", help="fused pool-to-pool kernel (no staging)")
+    ap.add_argument("--sync", action="store_true", help="every call waits for its device work")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tune", default="", help="comma list key=value for mp_set_tunable")
     args = ap.parse_args()
@@ -123,9 +124,12 @@ def main():
     L, H, D, bs, e = geom.L, geom.H, geom.D, geom.bs, geom.e
 
     # staging holds one whole turn batch (<= 64 sessions * 49 blocks)
+    # The two pools stand for two instances, so each gets its own stream: the sender's
+    # transmission runs on the source stream, the receiver's hashing on the destination stream.
     staging_blocks = n_sessions * ((512 + 256 + bs - 1) // bs + 2)
-    src = TorchPool(L, H, D, bs, e, geom.NB, staging_blocks=staging_blocks)
-    dst = TorchPool(L, H, D, bs, e, geom.NB)
+    s_src, s_dst = torch.cuda.Stream(), torch.cuda.Stream()
+    src = TorchPool(L, H, D, bs, e, geom.NB, staging_blocks=staging_blocks, stream=s_src)
+    dst = TorchPool(L, H, D, bs, e, geom.NB, stream=s_dst)
     # KV fill: N(0,1) in the model dtype, plane by plane (harness work, not the path)
     torch.manual_seed(args.config)
     tdt = torch.bfloat16 if geom.dtype == "bf16" else torch.float16
@@ -142,16 +146,20 @@ def main():
         for p in (src, dst):
             assert M.mp_set_tunable(p.h, k, int(v)) == 0
 
-    flags = M.MP_EVICT_ON_DEMAND | (M.MP_DIRECT if args.direct else 0)
+    # MP_ASYNC: a call returns once its device work is enqueued, so the host side of step k+1
+    # (match, allocation, table upload) overlaps the copy kernels of step k; the timed region
+    # ends with a device synchronisation.
+    flags = M.MP_EVICT_ON_DEMAND | (M.MP_DIRECT if args.direct else 0) | (0 if args.sync else M.MP_ASYNC)
     total_steps = args.warmup + args.steps
     n_epochs = (total_steps + n_turns - 1) // n_turns
     epochs = [build_epoch(W, geom, ep, n_sessions, n_turns) for ep in range(n_epochs)]
     rng = np.random.default_rng(args.config)
+    perms = [rng.permutation(geom.NB).astype(np.int32) for _ in range(total_steps)]
     state = dict(held=[])
 
     def do_step(i):
         ep, t = divmod(i, n_turns)
-        moved = run_step(M, src, dst, epochs[ep][t], rng, state, flags)
+        moved = run_step(M, src, dst, epochs[ep][t], perms[i], state, flags)
         hashed = int(((epochs[ep][t]["tok_off"][1:] - epochs[ep][t]["tok_off"][:-1]) // bs).sum())
         if t == n_turns - 1:       # the sessions end: everything they held becomes historical
             for ids in state["held"]:
@@ -224,6 +232,7 @@ def main():
             "geometry": f"L={L} H={H} D={D} bs={bs} {geom.dtype}, F={geom.F} B={geom.B}, "
                         f"pools {geom.NB} blocks ({geom.pool_bytes() / 2**30:.0f} GiB) each",
             "path": "direct (fused pool->pool)" if args.direct else "staged (gather -> staging -> scatter)",
+            "calls": "synchronous" if args.sync else "MP_ASYNC (host work of the next step overlaps the copy kernels)",
             "blocks_moved": moved,
             "payload_GiB": round(payload / 2**30, 3),
         },

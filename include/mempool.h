@@ -191,10 +191,12 @@ int mp_profile_enable(mp_pool_t *p, int on);
 int mp_profile_read(mp_pool_t *p, int kind, double *total_ms_out, uint64_t *launches_out,
                     uint64_t *bytes_out);
 
-/* Kernel launch-shape knobs (for tuning sweeps; defaults are chosen per geometry).
+/* Kernel launch-shape knobs (for tuning sweeps; defaults are chosen per geometry, and the
+ * value -1 restores the default).
  * key: "order" (0 record-major, 1 plane-major), "unroll" (1,2,4,8), "wg_per_cu" (0 = one
  * workgroup per tile group, >0 = persistent grid of that many workgroups per CU),
- * "nontemporal" (0/1). */
+ * "nontemporal" (0/1), "waves_per_wg" (1 or 4), "xcd_contiguous" (0/1: each XCD walks one
+ * contiguous eighth of the work instead of every eighth workgroup). */
 int mp_set_tunable(mp_pool_t *p, const char *key, int value);
 
 /* Calibration yardstick: one contiguous device-to-device copy of `bytes` (multiple of 16;

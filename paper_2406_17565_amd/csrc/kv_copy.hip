@@ -25,6 +25,16 @@ FastDiv make_fastdiv(uint32_t d) {
   return f;
 }
 
+CopyTune default_tune(CopyTune t, uint64_t frag_bytes, bool both_sides_tabled) {
+  if (t.order < 0) t.order = both_sides_tabled ? 1 : 0;
+  if (t.unroll < 0) t.unroll = 1;
+  if (t.wg_per_cu < 0) t.wg_per_cu = 0;
+  if (t.nontemporal < 0) t.nontemporal = 1;
+  if (t.waves_per_wg < 0) t.waves_per_wg = 1;
+  if (t.xcd_contiguous < 0) t.xcd_contiguous = frag_bytes >= (64u << 10) ? 1 : 0;
+  return t;
+}
+
 namespace {
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -38,27 +48,34 @@ struct CopyArgs {
   uint32_t frag_vecs;  // F / 16
   uint32_t n_planes;
   uint32_t n_entries;
+  uint32_t order;      // 0: entry-major walk, 1: plane-major walk
+  uint32_t xcd_span;   // workgroups per XCD for the contiguous re-mapping, 0 = off
   FastDiv by_chunks;   // / chunks_per_frag
   FastDiv by_inner;    // / n_planes (order 0) or / n_entries (order 1)
 };
 
 // The tables are separate restrict-qualified read-only arguments so that the wave-uniform
 // id loads can be issued as scalar loads.  (A table never aliases pool or staging memory.)
-template <int U, int ORDER, bool NT>
-__global__ __launch_bounds__(256) void kv_block_copy(const CopyArgs a,
-                                                     const int32_t *__restrict__ src_tbl,
-                                                     const int32_t *__restrict__ dst_tbl) {
+// W = wavefronts per workgroup.  Workgroups are dealt round-robin to the 8 XCDs in launch
+// order; with a.xcd_span > 0 the workgroup index is re-mapped so that each XCD walks one
+// contiguous eighth of the item space instead of every eighth item.
+template <int U, bool NT, int W>
+__global__ __launch_bounds__(64 * W) void kv_block_copy(const CopyArgs a,
+                                                        const int32_t *__restrict__ src_tbl,
+                                                        const int32_t *__restrict__ dst_tbl) {
   const uint32_t lane = threadIdx.x & 63u;
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const uint32_t step = gridDim.x * 4u;
-  for (uint32_t item = blockIdx.x * 4u + wave; item < a.n_items; item += step) {
+  const uint32_t wave = W == 1 ? 0u : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t step = gridDim.x * W;
+  uint32_t wg = blockIdx.x;
+  if (a.xcd_span && wg < 8u * a.xcd_span) wg = (wg & 7u) * a.xcd_span + (wg >> 3);
+  for (uint32_t item = wg * W + wave; item < a.n_items; item += step) {
     // wave-uniform decomposition: item = (outer * inner_count + inner) * chunks + c
     const uint32_t q = fastdiv(item, a.by_chunks);
     const uint32_t c = item - q * a.by_chunks.d;
     const uint32_t o = fastdiv(q, a.by_inner);
     const uint32_t r = q - o * a.by_inner.d;
-    const uint32_t i = ORDER == 0 ? o : r;  // table entry
-    const uint32_t p = ORDER == 0 ? r : o;  // plane = layer * 2 + (K|V)
+    const uint32_t i = a.order == 0 ? o : r;  // table entry
+    const uint32_t p = a.order == 0 ? r : o;  // plane = layer * 2 + (K|V)
     const uint32_t sid = __builtin_amdgcn_readfirstlane(src_tbl ? (uint32_t)src_tbl[i] : i);
     const uint32_t did = __builtin_amdgcn_readfirstlane(dst_tbl ? (uint32_t)dst_tbl[i] : i);
     const u32x4 *s = reinterpret_cast<const u32x4 *>(a.src_base + p * a.src_plane_stride +
@@ -83,55 +100,51 @@ __global__ __launch_bounds__(256) void kv_block_copy(const CopyArgs a,
   }
 }
 
-// Contiguous copy with the same per-lane shape (4 x 16-byte loads in flight, streaming
-// loads and stores): the yardstick for what a pure copy reaches on this GPU, and the kernel
-// whose hardware-counter readings calibrate the traffic figures of the table-driven copy.
-__global__ __launch_bounds__(256) void plain_copy_kernel(const u32x4 *__restrict__ src,
-                                                         u32x4 *__restrict__ dst, uint64_t n_vecs) {
-  const uint64_t base = (uint64_t)blockIdx.x * 1024u + threadIdx.x;
-  u32x4 reg[4];
-#pragma unroll
-  for (int u = 0; u < 4; ++u)
-    if (base + 256u * u < n_vecs) reg[u] = __builtin_nontemporal_load(src + base + 256u * u);
-#pragma unroll
-  for (int u = 0; u < 4; ++u)
-    if (base + 256u * u < n_vecs) __builtin_nontemporal_store(reg[u], dst + base + 256u * u);
+// Contiguous copy with the default per-lane shape of the table-driven kernel (one-wave
+// workgroups, one streaming 16-byte load and store per lane): the yardstick for what a pure
+// copy reaches on this GPU, and the kernel whose hardware-counter readings calibrate the
+// traffic figures of the table-driven copy.
+__global__ __launch_bounds__(64) void plain_copy_kernel(const u32x4 *__restrict__ src,
+                                                        u32x4 *__restrict__ dst, uint64_t n_vecs) {
+  const uint64_t v = (uint64_t)blockIdx.x * 64u + threadIdx.x;
+  if (v < n_vecs) __builtin_nontemporal_store(__builtin_nontemporal_load(src + v), dst + v);
 }
 
-template <int U, int ORDER>
+template <int U, int W>
 hipError_t launch_nt(const CopyArgs &a, const int32_t *st, const int32_t *dt, bool nt, dim3 grid,
                      hipStream_t stream) {
   if (nt)
-    hipLaunchKernelGGL((kv_block_copy<U, ORDER, true>), grid, dim3(256), 0, stream, a, st, dt);
+    hipLaunchKernelGGL((kv_block_copy<U, true, W>), grid, dim3(64 * W), 0, stream, a, st, dt);
   else
-    hipLaunchKernelGGL((kv_block_copy<U, ORDER, false>), grid, dim3(256), 0, stream, a, st, dt);
+    hipLaunchKernelGGL((kv_block_copy<U, false, W>), grid, dim3(64 * W), 0, stream, a, st, dt);
   return hipGetLastError();
 }
 
 template <int U>
-hipError_t launch_order(const CopyArgs &a, const int32_t *st, const int32_t *dt, int order,
+hipError_t launch_waves(const CopyArgs &a, const int32_t *st, const int32_t *dt, int waves,
                         bool nt, dim3 grid, hipStream_t stream) {
-  return order == 0 ? launch_nt<U, 0>(a, st, dt, nt, grid, stream)
-                    : launch_nt<U, 1>(a, st, dt, nt, grid, stream);
+  return waves == 1 ? launch_nt<U, 1>(a, st, dt, nt, grid, stream)
+                    : launch_nt<U, 4>(a, st, dt, nt, grid, stream);
 }
 
 }  // namespace
 
 hipError_t launch_plain_copy(void *dst, const void *src, uint64_t bytes, hipStream_t stream) {
   if (bytes == 0) return hipSuccess;
-  if (!dst || !src || (bytes & 15u) || (bytes >> 4) > 0x7fffffffull * 1024ull)
+  if (!dst || !src || (bytes & 15u) || (bytes >> 4) > 0x7fffffffull * 64ull)
     return hipErrorInvalidValue;
   const uint64_t n_vecs = bytes >> 4;
-  const uint64_t wgs = (n_vecs + 1023u) / 1024u;
-  hipLaunchKernelGGL(plain_copy_kernel, dim3((uint32_t)wgs), dim3(256), 0, stream,
+  const uint64_t wgs = (n_vecs + 63u) / 64u;
+  hipLaunchKernelGGL(plain_copy_kernel, dim3((uint32_t)wgs), dim3(64), 0, stream,
                      (const u32x4 *)src, (u32x4 *)dst, n_vecs);
   return hipGetLastError();
 }
 
 hipError_t launch_block_copy(const CopySide &src, const CopySide &dst, uint32_t n,
-                             uint32_t n_planes, uint64_t frag_bytes, const CopyTune &tune,
+                             uint32_t n_planes, uint64_t frag_bytes, const CopyTune &tune_in,
                              int n_cus, hipStream_t stream) {
   if (n == 0) return hipSuccess;
+  const CopyTune tune = default_tune(tune_in, frag_bytes, src.tbl != nullptr && dst.tbl != nullptr);
   if (!src.base || !dst.base || n_planes == 0 || frag_bytes == 0 || (frag_bytes & 15u) ||
       (frag_bytes >> 4) > 0x7fffffffull)
     return hipErrorInvalidValue;
@@ -164,19 +177,22 @@ hipError_t launch_block_copy(const CopySide &src, const CopySide &dst, uint32_t 
     a.n_entries = cnt;
     a.by_chunks = make_fastdiv(chunks);
     a.by_inner = make_fastdiv(tune.order == 0 ? n_planes : cnt);
-    uint32_t wgs = (a.n_items + 3u) / 4u;
+    a.order = (uint32_t)tune.order;
+    const uint32_t W = tune.waves_per_wg == 1 ? 1u : 4u;
+    uint32_t wgs = (a.n_items + W - 1u) / W;
     if (tune.wg_per_cu > 0) {
       const uint64_t cap = (uint64_t)tune.wg_per_cu * (uint64_t)(n_cus > 0 ? n_cus : 256);
       if (wgs > cap) wgs = (uint32_t)cap;
     }
+    a.xcd_span = tune.xcd_contiguous ? wgs / 8u : 0u;
     const dim3 grid(wgs);
     const bool nt = tune.nontemporal != 0;
     hipError_t e;
     switch (U) {
-      case 1: e = launch_order<1>(a, st, dt, tune.order, nt, grid, stream); break;
-      case 2: e = launch_order<2>(a, st, dt, tune.order, nt, grid, stream); break;
-      case 4: e = launch_order<4>(a, st, dt, tune.order, nt, grid, stream); break;
-      default: e = launch_order<8>(a, st, dt, tune.order, nt, grid, stream); break;
+      case 1: e = launch_waves<1>(a, st, dt, (int)W, nt, grid, stream); break;
+      case 2: e = launch_waves<2>(a, st, dt, (int)W, nt, grid, stream); break;
+      case 4: e = launch_waves<4>(a, st, dt, (int)W, nt, grid, stream); break;
+      default: e = launch_waves<8>(a, st, dt, (int)W, nt, grid, stream); break;
     }
     if (e != hipSuccess) return e;
   }

@@ -19,12 +19,22 @@ struct CopySide {
   uint64_t block_stride = 0;
 };
 
+// Launch shape of the copy kernel.  -1 = choose from the geometry (see default_tune).
 struct CopyTune {
-  int order = 0;        // 0: walk records (entry-major), 1: walk planes (plane-major)
-  int unroll = 4;       // 16-byte loads in flight per lane: 1, 2, 4 or 8
-  int wg_per_cu = 0;    // 0: one pass, a workgroup per 4 wave-items; >0: persistent grid
-  int nontemporal = 1;  // stream past the caches
+  int order = -1;           // 0: walk records (entry-major), 1: walk planes (plane-major)
+  int unroll = -1;          // 16-byte loads in flight per lane: 1, 2, 4 or 8
+  int wg_per_cu = -1;       // 0: one pass over the items; >0: persistent grid of that many WGs per CU
+  int nontemporal = -1;     // stream past the caches
+  int waves_per_wg = -1;    // 1 or 4 wavefronts per workgroup
+  int xcd_contiguous = -1;  // 1: each XCD walks one contiguous eighth of the work items
 };
+
+// Fills every field of `t` that is still -1.  Measured on MI355X (sweeps over all five
+// geometries): one 16-byte load per lane and one-wave workgroups give the most bandwidth
+// (many small independent waves beat deep unrolling); walking records is best when one side
+// is contiguous staging, walking planes when both sides are pools (fused copy); the per-XCD
+// contiguous walk helps for fragments of 64 KiB and more.
+CopyTune default_tune(CopyTune t, uint64_t frag_bytes, bool both_sides_tabled);
 
 // Unsigned division by an invariant divisor for numerators below 2^31:
 // x / d == (x * m) >> s.

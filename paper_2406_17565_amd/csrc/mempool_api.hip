@@ -71,7 +71,6 @@ struct mp_pool {
   PoolIndex idx;
   DeviceCtx dev;
   CopyTune tune;
-  bool tune_order_set = false;
   std::string err;
   mp_recv_cb cb = nullptr;
   void *cb_user = nullptr;
@@ -882,10 +881,13 @@ int mp_plain_copy(void *dst, const void *src, uint64_t bytes, void *stream, doub
 int mp_set_tunable(mp_pool_t *p, const char *key, int value) {
   if (!p || !key) return MP_EINVAL;
   const std::string k(key);
-  if (k == "order" && (value == 0 || value == 1)) p->tune.order = value;
-  else if (k == "unroll" && (value == 1 || value == 2 || value == 4 || value == 8)) p->tune.unroll = value;
-  else if (k == "wg_per_cu" && value >= 0 && value <= 64) p->tune.wg_per_cu = value;
-  else if (k == "nontemporal" && (value == 0 || value == 1)) p->tune.nontemporal = value;
+  const bool dflt = value == -1;  // -1 restores the geometry-based default
+  if (k == "order" && (dflt || value == 0 || value == 1)) p->tune.order = value;
+  else if (k == "unroll" && (dflt || value == 1 || value == 2 || value == 4 || value == 8)) p->tune.unroll = value;
+  else if (k == "wg_per_cu" && value >= -1 && value <= 64) p->tune.wg_per_cu = value;
+  else if (k == "nontemporal" && (dflt || value == 0 || value == 1)) p->tune.nontemporal = value;
+  else if (k == "waves_per_wg" && (dflt || value == 1 || value == 4)) p->tune.waves_per_wg = value;
+  else if (k == "xcd_contiguous" && (dflt || value == 0 || value == 1)) p->tune.xcd_contiguous = value;
   else return fail(p, MP_EINVAL, "unknown tunable or value out of range");
   return MP_OK;
 }
