@@ -1,0 +1,270 @@
+"""GPU parity at the full sizes of configurations 2-5, in the launch shape bench.py times
+(batched, asynchronous calls on per-pool streams).
+
+At these sizes a dense CPU copy of the pools does not fit a test, so the check is split:
+  * control plane (block ids handed out, match results, pool statistics): the oracle runs the
+    very same calls on pools of the same block size and block count but one-element-wide
+    fragments -- allocation, index and eviction do not depend on the fragment size;
+  * data plane: for a seeded sample of table entries the source blocks are fetched from the
+    GPU, pushed through the oracle's own gather / scatter, and compared byte for byte with the
+    destination blocks on the GPU;
+  * untouched blocks: 64-bit integer checksums of every (plane, block) fragment of the
+    destination pool, taken on the GPU before and after, must be unchanged outside the
+    destination table.
+"""
+import numpy as np
+import pytest
+
+from oracle import oracle as O
+from paper_2406_17565_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: -m gpu tests need a real MI355X")
+    from paper_2406_17565_amd import mempool as M
+    from paper_2406_17565_amd.pool import TorchPool
+    return M, TorchPool
+
+
+def fill_random(pool):
+    """Any bytes will do for a copy; int32 noise is the fastest fill torch has."""
+    v = pool.mem.view(torch.int32)
+    step = 1 << 28
+    for off in range(0, v.numel(), step):
+        v[off:off + step].random_()
+    torch.cuda.synchronize()
+
+
+def checksums(pool):
+    L2 = 2 * pool.geom[0]
+    return pool.mem.view(torch.int64).view(L2, pool.NB, pool.F // 8).sum(dim=2)
+
+
+def blocks_of(pool, ids):
+    """[len(ids), 2L, F] bytes of the given blocks, on the host."""
+    L2 = 2 * pool.geom[0]
+    idx = torch.as_tensor(np.asarray(ids, dtype=np.int64), device=pool.mem.device)
+    if pool.tier == 0:
+        x = pool.mem.view(L2, pool.NB, pool.F)[:, idx, :].permute(1, 0, 2)
+    else:
+        x = pool.mem.view(pool.NB, L2, pool.F)[idx.cpu()]
+    return x.contiguous().cpu().numpy()
+
+
+def check_sample(geom, src, dst, src_tbl, dst_tbl, rng, k=24):
+    """Oracle-computed destination blocks for k sampled table entries == GPU destination blocks."""
+    torch.cuda.synchronize()
+    n = len(src_tbl)
+    if n == 0:
+        return
+    pick = rng.choice(n, size=min(k, n), replace=False)
+    L, H, D, bs, e = geom
+    k = len(pick)
+    src_blocks = blocks_of(src, src_tbl[pick])                       # [k, 2L, F]
+    o_src = O.OraclePool(L, H, D, bs, e, k,
+                         data=np.ascontiguousarray(src_blocks.transpose(1, 0, 2)).reshape(-1))
+    o_dst = O.OraclePool(L, H, D, bs, e, k)
+    o_src.alloc(k)
+    perm = rng.permutation(k).astype(np.int32)
+    o_dst.alloc(k)
+    rc, _ = O.transfer(o_src, o_dst, np.arange(k), perm, flags=O.DST_GIVEN)
+    assert rc == 0
+    want = o_dst.data.reshape(2 * L, k, src.F).transpose(1, 0, 2)[perm]   # entry j -> block perm[j]
+    got = blocks_of(dst, dst_tbl[pick])
+    assert np.array_equal(got, want)
+
+
+class Mirror:
+    """Oracle pools with one-element fragments that replay the control plane."""
+
+    def __init__(self, bs, NB_src, NB_dst):
+        self.src = O.OraclePool(1, 1, 8, bs, 1, NB_src)
+        self.dst = O.OraclePool(1, 1, 8, bs, 1, NB_dst)
+        self.src.alloc(NB_src)
+
+
+def make_pools(gpu, g, NB_src, NB_dst, staging_blocks):
+    M, TorchPool = gpu
+    geom = (g.L, g.H, g.D, g.bs, g.e)
+    s_src, s_dst = torch.cuda.Stream(), torch.cuda.Stream()
+    src = TorchPool(*geom, NB_src, staging_blocks=staging_blocks, stream=s_src)
+    dst = TorchPool(*geom, NB_dst, stream=s_dst)
+    fill_random(src)
+    fill_random(dst)
+    assert M.mp_alloc(src.h, NB_src)[0] == 0
+    return geom, src, dst
+
+
+def release(*pools):
+    for p in pools:
+        p.close()
+        p.mem = p.staging = None
+    torch.cuda.empty_cache()
+
+
+def test_config3_multiturn_sessions(gpu):
+    """Llama-3-8B GQA shape, 16384-block pools, 64 sessions x 4 turns exactly as bench.py runs
+    them: mp_match_batch (pin) then asynchronous mp_transfer_with_insert_batch per turn."""
+    M, TorchPool = gpu
+    g = W.CONFIGS[3]
+    geom, src, dst = make_pools(gpu, g, g.NB, g.NB, staging_blocks=64 * 50)
+    mir = Mirror(g.bs, g.NB, g.NB)
+    rng = np.random.default_rng(33)
+    sessions = W.multiturn_sessions(seed=3)
+    flags = M.MP_EVICT_ON_DEMAND | M.MP_ASYNC
+    held, held_o, moved = [], [], []
+    for t in range(4):
+        prompts = [sessions[s][t] for s in range(64)]
+        toks, tok_off = W.csr(prompts)
+        nblk = np.array([(len(p) + g.bs - 1) // g.bs for p in prompts], np.uint32)
+        cap_off = np.concatenate([[0], np.cumsum(nblk)]).astype(np.uint32)
+        rc, mb, m = M.mp_match_batch(dst.h, toks, tok_off, cap_off, M.MP_MATCH_PIN)
+        assert rc == 0
+        mo = [mir.dst.match(p, flags=O.MATCH_PIN)[1] for p in prompts]
+        assert m.tolist() == [len(x) for x in mo]
+        assert all(mb[cap_off[r]:cap_off[r] + m[r]].tolist() == mo[r].tolist() for r in range(64))
+        blk_off = np.concatenate([[0], np.cumsum(nblk - m)]).astype(np.uint32)
+        src_tbl = rng.permutation(g.NB)[: int(blk_off[-1])].astype(np.int32)
+        before = checksums(dst)
+        rc, d = M.mp_transfer_with_insert_batch(src.h, dst.h, toks, tok_off, m, src_tbl, blk_off, flags)
+        assert rc == 0, M.mp_last_error(src.h)
+        rco, d_o = O.transfer_with_insert_batch(mir.src, mir.dst, toks, tok_off, m, src_tbl, blk_off,
+                                                flags=O.EVICT_ON_DEMAND)
+        assert rco == 0 and d.tolist() == d_o.tolist()
+        check_sample(geom, src, dst, src_tbl, d, rng)
+        after = checksums(dst)
+        untouched = torch.ones(g.NB, dtype=torch.bool, device="cuda")
+        untouched[torch.as_tensor(d.astype(np.int64), device="cuda")] = False
+        assert torch.equal(before[:, untouched], after[:, untouched])
+        assert not torch.equal(before[:, ~untouched], after[:, ~untouched])
+        assert dst.stats() == mir.dst.stats()
+        moved.append(len(d))
+    # the volumes of the recipe: first turn moves whole prompts, later turns only the new suffix
+    assert moved[0] == sum((len(sessions[s][0]) + 15) // 16 for s in range(64))
+    assert all(moved[t] < sum((len(sessions[s][t]) + 15) // 16 for s in range(64)) for t in (1, 2, 3))
+    release(src, dst)
+
+
+def test_config2_lognormal_requests(gpu):
+    """Llama-2-7B shape (128 KiB fragments), 8192-block pools (64 GiB each), 16 requests with
+    log-normal lengths, fragmented tables; per-request calls and one batched call."""
+    M, TorchPool = gpu
+    g = W.CONFIGS[2]
+    geom, src, dst = make_pools(gpu, g, g.NB, g.NB, staging_blocks=100)
+    mir = Mirror(g.bs, g.NB, g.NB)
+    rng = np.random.default_rng(22)
+    # fragment the destination free list: allocate everything, release in random order
+    ids = M.mp_alloc(dst.h, g.NB)[1]
+    mir.dst.alloc(g.NB)
+    order = rng.permutation(g.NB).astype(np.int32)
+    assert M.mp_free(dst.h, ids[order]) == mir.dst.free(ids[order]) == 0
+    lengths = W.lognormal_lengths()
+    prompts = W.random_prompts(2, lengths, g.vocab)
+    for r, p in enumerate(prompts[:6]):          # per-request calls (several staging rounds for long ones)
+        nb = (len(p) + g.bs - 1) // g.bs
+        tbl = rng.permutation(g.NB)[:nb].astype(np.int32)
+        rc, d = M.mp_transfer_with_insert(src.h, dst.h, p, 0, tbl)
+        rco, d_o = O.transfer_with_insert(mir.src, mir.dst, p, 0, tbl)
+        assert rc == rco == 0 and d.tolist() == d_o.tolist()
+        check_sample(geom, src, dst, tbl, d, rng, k=8)
+        assert M.mp_match(dst.h, p, nb)[1].tolist() == mir.dst.match(p)[1].tolist() == d[: len(p) // g.bs].tolist()
+    rest = prompts[6:]
+    toks, tok_off = W.csr(rest)
+    nblk = np.array([(len(p) + g.bs - 1) // g.bs for p in rest], np.uint32)
+    blk_off = np.concatenate([[0], np.cumsum(nblk)]).astype(np.uint32)
+    tbl = rng.permutation(g.NB)[: int(blk_off[-1])].astype(np.int32)
+    before = checksums(dst)
+    rc, d = M.mp_transfer_with_insert_batch(src.h, dst.h, toks, tok_off, np.zeros(len(rest), np.uint32),
+                                            tbl, blk_off, M.MP_ASYNC)
+    rco, d_o = O.transfer_with_insert_batch(mir.src, mir.dst, toks, tok_off, np.zeros(len(rest), np.uint32),
+                                            tbl, blk_off)
+    assert rc == rco == 0 and d.tolist() == d_o.tolist()
+    check_sample(geom, src, dst, tbl, d, rng, k=16)
+    after = checksums(dst)
+    untouched = torch.ones(g.NB, dtype=torch.bool, device="cuda")
+    untouched[torch.as_tensor(d.astype(np.int64), device="cuda")] = False
+    assert torch.equal(before[:, untouched], after[:, untouched])
+    assert dst.stats() == mir.dst.stats()
+    release(src, dst)
+
+
+def test_config4_long_context_with_eviction(gpu):
+    """Llama-2-13B shape (320 KiB fragments, 25 MiB records), 32 requests of 16384 tokens, 90 %
+    sharing an 8192-token prefix; the 4096-block destination overflows and evicts on demand."""
+    M, TorchPool = gpu
+    g = W.CONFIGS[4]
+    NB_src, NB_dst = 1024, 4096
+    geom, src, dst = make_pools(gpu, g, NB_src, NB_dst, staging_blocks=128)
+    mir = Mirror(g.bs, NB_src, NB_dst)
+    rng = np.random.default_rng(44)
+    moved = []
+    for r, p in enumerate(W.long_context_requests()):
+        nb = len(p) // g.bs
+        rc, m = M.mp_match(dst.h, p, nb, M.MP_MATCH_PIN)
+        rco, mo = mir.dst.match(p, flags=O.MATCH_PIN)
+        assert rc == rco == 0 and m.tolist() == mo.tolist()
+        tbl = rng.permutation(NB_src)[: nb - len(m)].astype(np.int32)
+        fl = M.MP_EVICT_ON_DEMAND | (M.MP_ASYNC if r % 2 else 0)
+        rc, d = M.mp_transfer_with_insert(src.h, dst.h, p, len(m), tbl, flags=fl)
+        rco, d_o = O.transfer_with_insert(mir.src, mir.dst, p, len(mo), tbl, flags=O.EVICT_ON_DEMAND)
+        assert rc == rco == 0 and d.tolist() == d_o.tolist(), M.mp_last_error(src.h)
+        if r % 4 == 0:
+            check_sample(geom, src, dst, tbl, d, rng, k=4)
+        ids = np.concatenate([m, d])
+        assert M.mp_free(dst.h, ids) == mir.dst.free(ids) == 0          # the request finishes
+        assert dst.stats() == mir.dst.stats()
+        moved.append(len(d))
+    assert sorted(set(moved)) == [256, 512] and moved.count(256) == 28   # 29 sharers, the first moves 512
+    assert dst.stats()["n_free"] < 512                                   # the pool did overflow
+    release(src, dst)
+
+
+def test_config5_tp_share_and_host_tier(gpu):
+    """One GPU's share of a 70B model: 160 fragments of 4 KiB per block.  256 requests of 2048
+    tokens in one batched call through a staging buffer eight times smaller than the batch, then
+    a slice of it out to a pinned-host pool and back."""
+    M, TorchPool = gpu
+    g = W.CONFIGS[5]
+    geom, src, dst = make_pools(gpu, g, g.NB, g.NB, staging_blocks=4096)
+    mir = Mirror(g.bs, g.NB, g.NB)
+    rng = np.random.default_rng(55)
+    prompts = W.random_prompts(5, [2048] * 256, g.vocab)
+    toks, tok_off = W.csr(prompts)
+    blk_off = (np.arange(257) * 128).astype(np.uint32)
+    tbl = rng.permutation(g.NB)[: 256 * 128].astype(np.int32)
+    before = checksums(dst)
+    first = np.zeros(256, np.uint32)
+    rc, d = M.mp_transfer_with_insert_batch(src.h, dst.h, toks, tok_off, first, tbl, blk_off, M.MP_ASYNC)
+    rco, d_o = O.transfer_with_insert_batch(mir.src, mir.dst, toks, tok_off, first, tbl, blk_off)
+    assert rc == rco == 0 and d.tolist() == d_o.tolist(), M.mp_last_error(src.h)
+    check_sample(geom, src, dst, tbl, d, rng, k=64)
+    after = checksums(dst)
+    untouched = torch.ones(g.NB, dtype=torch.bool, device="cuda")
+    untouched[torch.as_tensor(d.astype(np.int64), device="cuda")] = False
+    assert torch.equal(before[:, untouched], after[:, untouched])
+    assert dst.stats() == mir.dst.stats()
+    rc, mb, m = M.mp_match_batch(dst.h, toks, tok_off, blk_off)
+    assert rc == 0 and m.tolist() == [128] * 256 and mb.tolist() == d.tolist()
+
+    # host tier: 2048 blocks (1.25 GiB) out to pinned memory and back in
+    host = TorchPool(*geom, 2048, tier=M.MP_TIER_HOST_PINNED)
+    o_host = O.OraclePool(1, 1, 8, g.bs, 1, 2048, tier=O.TIER_HOST)
+    pick = rng.permutation(256 * 128)[:2048]
+    rc, h_ids = M.mp_transfer(dst.h, host.h, d[pick])       # dst has no staging -> refused
+    assert rc == M.MP_ENOSTAGING
+    rc, h_ids = M.mp_transfer(src.h, host.h, tbl[pick])
+    rco, h_o = O.transfer(mir.src, o_host, tbl[pick])
+    assert rc == rco == 0 and h_ids.tolist() == h_o.tolist(), M.mp_last_error(src.h)
+    check_sample(geom, src, host, tbl[pick], h_ids, rng, k=32)
+    back = TorchPool(*geom, 2048, staging_blocks=256)
+    rc, b_ids = M.mp_transfer(host.h, back.h, h_ids)
+    assert rc == 0, M.mp_last_error(host.h)
+    check_sample(geom, host, back, h_ids, b_ids, rng, k=32)
+    check_sample(geom, src, back, tbl[pick], b_ids, rng, k=32)   # round trip = identity
+    release(src, dst, host, back)
