@@ -25,18 +25,32 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E peak
 
 
-def build_epoch(W, geom, epoch, n_sessions, n_turns):
-    """Tokens of every turn of one set of sessions (fresh ids per epoch => no cross-epoch hits)."""
-    sessions = W.multiturn_sessions(seed=3 + 1000 * epoch, n_sessions=n_sessions, n_turns=n_turns,
-                                    vocab=geom.vocab)
-    turns = []
-    for t in range(n_turns):
-        prompts = [sessions[s][t] for s in range(n_sessions)]
-        toks, tok_off = W.csr(prompts)
-        nblk = np.array([(len(p) + geom.bs - 1) // geom.bs for p in prompts], dtype=np.uint32)
-        cap_off = np.concatenate([[0], np.cumsum(nblk)]).astype(np.uint32)
-        turns.append(dict(toks=toks, tok_off=tok_off, nblk=nblk, cap_off=cap_off))
-    return turns
+def _turn(W, geom, prompts):
+    toks, tok_off = W.csr(prompts)
+    nblk = np.array([(len(p) + geom.bs - 1) // geom.bs for p in prompts], dtype=np.uint32)
+    cap_off = np.concatenate([[0], np.cumsum(nblk)]).astype(np.uint32)
+    return dict(toks=toks, tok_off=tok_off, nblk=nblk, cap_off=cap_off)
+
+
+def build_epoch(W, geom, cfg, epoch, n_sessions=64, n_turns=4):
+    """One epoch = the steps after which every request of the epoch has finished.  Token ids
+    are fresh per epoch, so nothing matches across epochs.
+      config 3: 4 steps, one per turn of 64 multi-turn sessions
+      config 2: 1 step, 16 requests with log-normal lengths
+      config 4: 32 steps, one 16384-token request each, 29 of them sharing an 8192-token prefix
+      config 5: 1 step, 256 requests of 2048 tokens"""
+    seed = cfg + 1000 * epoch
+    if cfg == 3:
+        sessions = W.multiturn_sessions(seed=seed, n_sessions=n_sessions, n_turns=n_turns,
+                                        vocab=geom.vocab)
+        return [_turn(W, geom, [sessions[s][t] for s in range(n_sessions)]) for t in range(n_turns)]
+    if cfg == 2:
+        return [_turn(W, geom, W.random_prompts(seed, W.lognormal_lengths(seed=seed), geom.vocab))]
+    if cfg == 4:
+        return [_turn(W, geom, [p]) for p in W.long_context_requests(seed=seed, vocab=geom.vocab)]
+    if cfg == 5:
+        return [_turn(W, geom, W.random_prompts(seed, [2048] * 256, geom.vocab))]
+    raise ValueError("config must be 2, 3, 4 or 5")
 
 
 def run_step(M, src, dst, turn, perm, state, flags):
@@ -67,7 +81,7 @@ def cpu_baseline(W, geom, n_sessions=16, n_turns=4, NB_src=2048, NB_dst=4096):
     src = O.OraclePool(geom.L, geom.H, geom.D, geom.bs, geom.e, NB_src, data=src_data)
     dst = O.OraclePool(geom.L, geom.H, geom.D, geom.bs, geom.e, NB_dst)
     src.alloc(NB_src)
-    turns = build_epoch(W, geom, 0, n_sessions, n_turns)
+    turns = build_epoch(W, geom, 3, 0, n_sessions, n_turns)
     moved = hashed = 0
     t_total = 0.0
     for turn in turns:
@@ -96,14 +110,60 @@ def cpu_baseline(W, geom, n_sessions=16, n_turns=4, NB_src=2048, NB_dst=4096):
                 seconds=round(t_total, 3), blocks_per_s=round(moved / t_total, 1))
 
 
+def host_tier(args):
+    """Config 5's variant: HBM pool -> pinned-host pool (gather kernel, then device-to-host
+    copies of records on the side stream) and back (host-to-device, then scatter kernel).
+    Bound by the host link, not by HBM; never used as the headline value."""
+    import torch
+    from paper_2406_17565_amd import mempool as M
+    from paper_2406_17565_amd import workloads as W
+    from paper_2406_17565_amd.pool import TorchPool
+    g = W.CONFIGS[5]
+    geom = (g.L, g.H, g.D, g.bs, g.e)
+    n = 4096                                            # 2.5 GiB per transfer
+    src = TorchPool(*geom, g.NB, staging_blocks=512)    # two slots of 160 MiB
+    host = TorchPool(*geom, n, tier=M.MP_TIER_HOST_PINNED)
+    src.mem.view(torch.int32).random_()
+    torch.cuda.synchronize()
+    assert M.mp_alloc(src.h, g.NB)[0] == 0
+    rng = np.random.default_rng(5)
+    out_t, in_t = [], []
+    for rep in range(args.steps or 5):
+        tbl = rng.permutation(g.NB)[:n].astype(np.int32)
+        t0 = time.perf_counter()
+        rc, h = M.mp_transfer(src.h, host.h, tbl)
+        out_t.append(time.perf_counter() - t0)
+        assert rc == 0, M.mp_last_error(src.h)
+        rc, back = M.mp_alloc(src.h, 0)
+        t0 = time.perf_counter()
+        rc, _ = M.mp_transfer(host.h, src.h, h, tbl, flags=M.MP_DST_GIVEN)   # swap back in place
+        in_t.append(time.perf_counter() - t0)
+        assert rc == 0, M.mp_last_error(host.h)
+        assert M.mp_free(host.h, h) == 0
+    payload = n * g.B
+    peak = 64.0
+    o, i = payload / min(out_t[1:]) / 1e9, payload / min(in_t[1:]) / 1e9
+    print(json.dumps({
+        "metric": "host-tier KV transfer GB/s (HBM <-> pinned host), 1 MI355X", "unit": "GB/s",
+        "value": round(o, 2), "hbm_to_host": round(o, 2), "host_to_hbm": round(i, 2),
+        "n_gpus": 1, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": f"config 5 ({g.name}): {n} blocks ({payload / 2**30:.2f} GiB) per "
+                               f"transfer through two 160 MiB staging slots"},
+        "roofline": {"bound": "pcie", "achieved": round(o, 2), "peak": peak, "unit": "GB/s",
+                     "frac": round(o / peak, 4), "note": "PCIe Gen5 x16, one direction"}}))
+    src.close()
+    host.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--direct", action="store_true", help="fused pool-to-pool kernel (no staging)")
     ap.add_argument("--sync", action="store_true", help="every call waits for its device work")
+    ap.add_argument("--host-tier", action="store_true", help="config 5 HBM <-> pinned-host variant")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tune", default="", help="comma list key=value for mp_set_tunable")
     args = ap.parse_args()
@@ -111,6 +171,13 @@ def main():
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
               "run it with --gpus 1", file=sys.stderr)
         sys.exit(2)
+
+    if args.host_tier:
+        return host_tier(args)
+    if args.steps is None:
+        args.steps = {2: 8, 3: 20, 4: 32, 5: 6}[args.config]
+    if args.warmup is None:
+        args.warmup = {2: 2, 3: 4, 4: 32, 5: 2}[args.config]
 
     import torch
     from paper_2406_17565_amd import mempool as M
@@ -120,16 +187,23 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     geom = W.CONFIGS[args.config]
-    n_sessions, n_turns = 64, 4
     L, H, D, bs, e = geom.L, geom.H, geom.D, geom.bs, geom.e
+    epoch0 = build_epoch(W, geom, args.config, 0)
+    n_turns = len(epoch0)
+    NB_src = 1024 if args.config == 4 else geom.NB   # config 4: the working set cannot be resident twice
+    NB_dst = geom.NB
 
-    # staging holds one whole turn batch (<= 64 sessions * 49 blocks)
     # The two pools stand for two instances, so each gets its own stream: the sender's
     # transmission runs on the source stream, the receiver's hashing on the destination stream.
-    staging_blocks = n_sessions * ((512 + 256 + bs - 1) // bs + 2)
+    # Staging: one whole step if that is below 8 GiB, else 4 GiB (the transfer runs in rounds).
+    if args.config == 3:   # per turn only the reply + new tokens (and a partial block) move
+        biggest = 64 * ((256 + 512 + bs - 1) // bs + 2)
+    else:
+        biggest = max(int(t["nblk"].sum()) for t in epoch0) + 64
+    staging_blocks = biggest if biggest * geom.B <= (8 << 30) else (4 << 30) // geom.B
     s_src, s_dst = torch.cuda.Stream(), torch.cuda.Stream()
-    src = TorchPool(L, H, D, bs, e, geom.NB, staging_blocks=staging_blocks, stream=s_src)
-    dst = TorchPool(L, H, D, bs, e, geom.NB, stream=s_dst)
+    src = TorchPool(L, H, D, bs, e, NB_src, staging_blocks=staging_blocks, stream=s_src)
+    dst = TorchPool(L, H, D, bs, e, NB_dst, stream=s_dst)
     # KV fill: N(0,1) in the model dtype, plane by plane (harness work, not the path)
     torch.manual_seed(args.config)
     tdt = torch.bfloat16 if geom.dtype == "bf16" else torch.float16
@@ -140,7 +214,7 @@ def main():
         view[off:off + n].normal_()
     dst.mem.zero_()
     torch.cuda.synchronize()
-    assert M.mp_alloc(src.h, geom.NB)[0] == 0      # the sender's engine owns all its blocks
+    assert M.mp_alloc(src.h, NB_src)[0] == 0       # the sender's engine owns all its blocks
     for kv in filter(None, args.tune.split(",")):
         k, v = kv.split("=")
         for p in (src, dst):
@@ -152,16 +226,18 @@ def main():
     flags = M.MP_EVICT_ON_DEMAND | (M.MP_DIRECT if args.direct else 0) | (0 if args.sync else M.MP_ASYNC)
     total_steps = args.warmup + args.steps
     n_epochs = (total_steps + n_turns - 1) // n_turns
-    epochs = [build_epoch(W, geom, ep, n_sessions, n_turns) for ep in range(n_epochs)]
+    epochs = [epoch0] + [build_epoch(W, geom, args.config, ep) for ep in range(1, n_epochs)]
     rng = np.random.default_rng(args.config)
-    perms = [rng.permutation(geom.NB).astype(np.int32) for _ in range(total_steps)]
+    perms = [rng.permutation(NB_src).astype(np.int32) for _ in range(total_steps)]
     state = dict(held=[])
 
     def do_step(i):
         ep, t = divmod(i, n_turns)
         moved = run_step(M, src, dst, epochs[ep][t], perms[i], state, flags)
         hashed = int(((epochs[ep][t]["tok_off"][1:] - epochs[ep][t]["tok_off"][:-1]) // bs).sum())
-        if t == n_turns - 1:       # the sessions end: everything they held becomes historical
+        # requests finish: everything they held becomes historical (config 3: sessions live
+        # through their four turns; the other configs' requests are single-shot)
+        if t == n_turns - 1 or args.config != 3:
             for ids in state["held"]:
                 assert M.mp_free(dst.h, ids) == 0
             state["held"].clear()
@@ -226,11 +302,16 @@ def main():
         "dtype": "u8",
         "data": "synthetic",
         "config": {
-            "workload": f"config {args.config} ({geom.name}): {n_sessions} multi-turn sessions x "
-                        f"{n_turns} turns, match then transfer_with_insert of the unmatched suffix, "
-                        f"one batched call per turn",
+            "workload": f"config {args.config} ({geom.name}): " + {
+                3: "64 multi-turn sessions x 4 turns, one batched call per turn",
+                2: "16 requests with log-normal lengths per step, one batched call",
+                4: "one 16384-token request per step, 29 of 32 share an 8192-token prefix, "
+                   "destination evicts on demand",
+                5: "256 requests of 2048 tokens per step, one batched call"}[args.config]
+                        + "; match, then transfer_with_insert of the unmatched suffix",
             "geometry": f"L={L} H={H} D={D} bs={bs} {geom.dtype}, F={geom.F} B={geom.B}, "
-                        f"pools {geom.NB} blocks ({geom.pool_bytes() / 2**30:.0f} GiB) each",
+                        f"pools {NB_src}/{NB_dst} blocks ({geom.pool_bytes(NB_src) / 2**30:.0f}/"
+                        f"{geom.pool_bytes(NB_dst) / 2**30:.0f} GiB), staging {staging_blocks} blocks",
             "path": "direct (fused pool->pool)" if args.direct else "staged (gather -> staging -> scatter)",
             "calls": "synchronous" if args.sync else "MP_ASYNC (host work of the next step overlaps the copy kernels)",
             "blocks_moved": moved,
@@ -257,7 +338,7 @@ def main():
                              for k, v in per_kind.items()},
         },
     }
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.config == 3:
         out["cpu_baseline"] = cpu_baseline(W, geom)
     print(json.dumps(out))
     src.close()
