@@ -76,7 +76,8 @@ typedef struct mp_pool mp_pool_t; /* opaque, library-owned */
 #define MP_ASYNC 0x04u            /* enqueue only; results valid in stream order              */
 #define MP_MATCH_PIN 0x08u        /* mp_match: take one reference on every returned block     */
 #define MP_TOKENS_ON_DEVICE 0x10u /* `tokens` is a device pointer (same device as the pool)   */
-#define MP_DIRECT 0x20u           /* HBM->HBM only: one fused kernel, no staging round trip   */
+#define MP_DIRECT 0x20u           /* one fused kernel, no staging round trip; with a pinned-host
+                                     pool at one end the kernel accesses host memory itself  */
 
 typedef struct {
   uint32_t n_layers, n_kv_heads, head_dim, block_size, elem_bytes;
@@ -128,8 +129,10 @@ int mp_evict(mp_pool_t *p, uint32_t n_blocks, uint32_t *n_evicted_out);
 /* transfer (Table 1, section 4.3): allocate n blocks at dst (unless MP_DST_GIVEN), then copy
  * block src_blocks[i] of src into block dst_blocks[i] of dst for all i (all 2*L fragments).
  * HBM->HBM: gather into src's staging, scatter from it (or one fused kernel with MP_DIRECT).
- * HBM->host: gather, then asynchronous device-to-host copies of records on the side stream.
- * host->HBM: host-to-device copies into dst's staging, then scatter.
+ * HBM->host: gather, then asynchronous device-to-host copies of records on the side stream
+ *           (with MP_DIRECT: one kernel that stores straight into the mapped host pool).
+ * host->HBM: host-to-device copies into dst's staging, then scatter (MP_DIRECT: one kernel
+ *           that loads straight from the mapped host pool).  host->host is not supported.
  * Transfers larger than the staging buffer are cut into staging-sized rounds.
  * src ids must be held or historical; given dst ids must be held and duplicate-free.
  * priv / priv_len: opaque user data handed to the receiver callback, never sent to the GPU. */

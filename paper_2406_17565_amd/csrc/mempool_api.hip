@@ -292,10 +292,7 @@ bool tables_overlap(const mp_pool *p, const int32_t *a, const int32_t *b, uint32
 int check_copy_feasible(mp_pool *src, mp_pool *dst, uint32_t n, uint32_t flags) {
   const bool s_hbm = src->desc.tier == MP_TIER_HBM, d_hbm = dst->desc.tier == MP_TIER_HBM;
   if (!s_hbm && !d_hbm) return fail(src, MP_ESHAPE, "host-to-host transfers are not supported");
-  if (flags & MP_DIRECT) {
-    if (!s_hbm || !d_hbm) return fail(src, MP_EINVAL, "MP_DIRECT needs two HBM pools");
-    return MP_OK;
-  }
+  if (flags & MP_DIRECT) return MP_OK;  // no staging: the kernel addresses both pools itself
   if (n == 0) return MP_OK;
   mp_pool *x = s_hbm ? src : dst;
   if (!x->desc.staging || x->desc.staging_bytes < x->B)
@@ -316,10 +313,15 @@ int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *
   const CopyTune tune = effective_tune(x);
   const uint64_t B = x->B;
   const int32_t *d_src = nullptr, *d_dst = nullptr;
-  rc = upload_tables(x, s_hbm ? src_ids : nullptr, d_hbm ? dst_ids : nullptr, n, &d_src, &d_dst);
+  const bool direct = (flags & MP_DIRECT) != 0;
+  rc = upload_tables(x, (s_hbm || direct) ? src_ids : nullptr, (d_hbm || direct) ? dst_ids : nullptr,
+                     n, &d_src, &d_dst);
   if (rc != MP_OK) return rc;
 
-  if (flags & MP_DIRECT) {  // one fused kernel: pool fragment -> pool fragment
+  if (direct) {
+    // One fused kernel, fragment to fragment.  With a pinned-host pool at one end the kernel
+    // reads or writes host memory through the host link itself (zero-copy): no staging write,
+    // no copy-engine hop.
     ProfScope ps(x, kProfDirect, 2ull * n * B);
     HIP_TRY(x, launch_block_copy(pool_side(src, d_src), pool_side(dst, d_dst), n, x->P, x->F,
                                  tune, d.n_cus, d.stream));

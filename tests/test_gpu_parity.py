@@ -395,6 +395,16 @@ def test_host_tier_both_directions(gpu):
     _same_state(ho, hg)
     assert M.mp_match(hg.h, t, 4)[1].tolist() == ho.match(t)[1].tolist()
     assert M.mp_transfer(hg.h, hg.h, [int(d3[0])])[0] == M.MP_ESHAPE   # host -> host unsupported
+    # zero-copy variants: the fused kernel stores into / loads from the mapped host pool itself
+    tbl2 = rng.integers(0, 48, 9).astype(np.int32)
+    rc, d4 = M.mp_transfer(sg.h, hg.h, tbl2, flags=M.MP_DIRECT)
+    rco, d4_o = O.transfer(so, ho, tbl2)
+    assert rc == rco == 0 and d4.tolist() == d4_o.tolist(), M.mp_last_error(sg.h)
+    _same_state(ho, hg)
+    rc, d5 = M.mp_transfer(hg.h, bg.h, d4, flags=M.MP_DIRECT)
+    rco, d5_o = O.transfer(ho, bo, d4_o)
+    assert rc == rco == 0 and d5.tolist() == d5_o.tolist(), M.mp_last_error(hg.h)
+    _same_state(bo, bg)
     for p in (sg, hg, bg):
         p.close()
 
