@@ -53,6 +53,35 @@ def build_epoch(W, geom, cfg, epoch, n_sessions=64, n_turns=4):
     raise ValueError("config must be 2, 3, 4 or 5")
 
 
+def run_step_by_layer(M, src, dst, turn, perm, state, flags, n_layers, bs):
+    """The by-layer flavour of a step: match, allocate once, ship one layer per call (as an
+    engine would while prefill advances), then insert the prompts."""
+    rc, mb, m = M.mp_match_batch(dst.h, turn["toks"], turn["tok_off"], turn["cap_off"],
+                                 M.MP_MATCH_PIN)
+    assert rc == 0, M.mp_last_error(dst.h)
+    need = turn["nblk"] - m
+    blk_off = np.concatenate([[0], np.cumsum(need)]).astype(np.int64)
+    total = int(blk_off[-1])
+    src_blocks = perm[:total]
+    rc, d = M.mp_alloc(dst.h, total, M.MP_EVICT_ON_DEMAND)
+    assert rc == 0, M.mp_last_error(dst.h)
+    for l in range(n_layers):
+        rc = M.mp_transfer_layers(src.h, dst.h, src_blocks, d, l, l + 1, flags)
+        assert rc == 0, M.mp_last_error(src.h)
+    rc, hashes, hoff = M.mp_block_hashes_batch(dst.h, turn["toks"], turn["tok_off"], bs)
+    assert rc == 0
+    held = [d]
+    for r in range(len(m)):
+        t = turn["toks"][turn["tok_off"][r]:turn["tok_off"][r + 1]]
+        known = mb[turn["cap_off"][r]:turn["cap_off"][r] + m[r]]
+        ids = np.concatenate([known, d[blk_off[r]:blk_off[r + 1]]])
+        rc, _ = M.mp_insert_hashed(dst.h, t, hashes[hoff[r]:hoff[r + 1]], ids)
+        assert rc == 0, M.mp_last_error(dst.h)
+        held.append(known)
+    state["held"].append(np.concatenate(held))
+    return total
+
+
 def run_step(M, src, dst, turn, perm, state, flags):
     """One step.  Returns the number of blocks moved."""
     rc, mb, m = M.mp_match_batch(dst.h, turn["toks"], turn["tok_off"], turn["cap_off"],
@@ -183,6 +212,8 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--direct", action="store_true", help="fused pool-to-pool kernel (no staging)")
     ap.add_argument("--sync", action="store_true", help="every call waits for its device work")
+    ap.add_argument("--by-layer", action="store_true",
+                    help="ship one layer per call (mp_transfer_layers) instead of whole blocks")
     ap.add_argument("--host-tier", action="store_true", help="config 5 HBM <-> pinned-host variant")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tune", default="", help="comma list key=value for mp_set_tunable")
@@ -253,7 +284,11 @@ def main():
 
     def do_step(i):
         ep, t = divmod(i, n_turns)
-        moved = run_step(M, src, dst, epochs[ep][t], perms[i], state, flags)
+        if args.by_layer:
+            moved = run_step_by_layer(M, src, dst, epochs[ep][t], perms[i], state,
+                                      flags & ~M.MP_EVICT_ON_DEMAND, L, bs)
+        else:
+            moved = run_step(M, src, dst, epochs[ep][t], perms[i], state, flags)
         hashed = int(((epochs[ep][t]["tok_off"][1:] - epochs[ep][t]["tok_off"][:-1]) // bs).sum())
         # requests finish: everything they held becomes historical (config 3: sessions live
         # through their four turns; the other configs' requests are single-shot)
@@ -333,6 +368,8 @@ def main():
                         f"pools {NB_src}/{NB_dst} blocks ({geom.pool_bytes(NB_src) / 2**30:.0f}/"
                         f"{geom.pool_bytes(NB_dst) / 2**30:.0f} GiB), staging {staging_blocks} blocks",
             "path": "direct (fused pool->pool)" if args.direct else "staged (gather -> staging -> scatter)",
+            "granularity": "by-layer (one mp_transfer_layers call per layer)" if args.by_layer
+                           else "by-request (whole blocks)",
             "calls": "synchronous" if args.sync else "MP_ASYNC (host work of the next step overlaps the copy kernels)",
             "blocks_moved": moved,
             "payload_GiB": round(payload / 2**30, 3),

@@ -140,6 +140,17 @@ int mp_transfer(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks,
                 int32_t *dst_blocks /* in with MP_DST_GIVEN, else out */, uint32_t n,
                 uint32_t flags, const void *priv, uint64_t priv_len);
 
+/* By-layer transfer (section 4.3: an explicit destination list "is particularly useful for
+ * constructing layer-by-layer transmissions"; section 5.2: by-layer vs by-request): copies only
+ * layers [layer_begin, layer_end) of every listed block, so an engine can ship a layer as soon
+ * as its prefill finished.  The destination ids are always given (allocate them once with
+ * mp_alloc before the first layer; insert with mp_insert after the last).  Staging holds packed
+ * records of 2*(layer_end-layer_begin) fragments.  With a host-tier pool at one end MP_DIRECT
+ * is required (else MP_ESHAPE). */
+int mp_transfer_layers(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks,
+                       const int32_t *dst_blocks, uint32_t n, uint32_t layer_begin,
+                       uint32_t layer_end, uint32_t flags);
+
 /* transfer_with_insert (Table 1, section 4.3): transfer, then the receiver inserts the prompt.
  * Blocks [0,first_block) of the prompt must already be in dst's index (else MP_ESTALE);
  * src_blocks / dst_blocks describe prompt blocks first_block .. first_block+n-1, and
@@ -166,6 +177,11 @@ int mp_transfer_with_insert_batch(mp_pool_t *src, mp_pool_t *dst, const uint32_t
  * library's convention): out[i] for i < floor(n_tokens/bs), computed by the device kernel. */
 int mp_block_hashes(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, uint64_t *out,
                     uint32_t flags);
+
+/* The same for n_req prompts in one kernel launch: prompt r's hashes are written back to back,
+ * floor(len_r/bs) each, in request order. */
+int mp_block_hashes_batch(mp_pool_t *p, const uint32_t *tokens, const uint32_t *tok_off,
+                          uint32_t n_req, uint64_t *out, uint32_t flags);
 
 /* Host-only forms of insert / match for callers that already hold the prompt's chained
  * hashes (e.g. computed once by mp_block_hashes where the request entered the cluster and

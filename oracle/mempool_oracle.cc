@@ -380,6 +380,34 @@ int orc_transfer(orc_pool_t *src, orc_pool_t *dst, const int32_t *src_blocks,
   return ORC_OK;
 }
 
+// By-layer transfer (section 4.3, explicit destination list for layer-by-layer transmission;
+// section 5.2, by-layer approach): only layers [l0, l1) of each listed block move.  All source
+// fragments are read before any destination fragment is written.
+int orc_transfer_layers(orc_pool_t *src, orc_pool_t *dst, const int32_t *src_blocks,
+                        const int32_t *dst_blocks, uint32_t n, uint32_t l0, uint32_t l1) {
+  if (!src || !dst || ((!src_blocks || !dst_blocks) && n)) return ORC_EINVAL;
+  if (!same_geometry(src, dst)) return ORC_ESHAPE;
+  if (l0 >= l1 || l1 > src->L) return ORC_EINVAL;
+  int rc = check_src_ids(src, src_blocks, n);
+  if (rc != ORC_OK) return rc;
+  rc = check_given_dst_ids(dst, dst_blocks, n);
+  if (rc != ORC_OK) return rc;
+  std::vector<uint8_t> tmp((size_t)n * 2 * (l1 - l0) * src->F);
+  size_t k = 0;
+  for (uint32_t i = 0; i < n; ++i)
+    for (uint32_t l = l0; l < l1; ++l)
+      for (uint32_t kv = 0; kv < 2; ++kv, ++k)
+        std::memcpy(&tmp[k * src->F],
+                    src->base + orc_fragment_offset(src, l, kv, (uint32_t)src_blocks[i]), src->F);
+  k = 0;
+  for (uint32_t i = 0; i < n; ++i)
+    for (uint32_t l = l0; l < l1; ++l)
+      for (uint32_t kv = 0; kv < 2; ++kv, ++k)
+        std::memcpy(dst->base + orc_fragment_offset(dst, l, kv, (uint32_t)dst_blocks[i]),
+                    &tmp[k * src->F], src->F);
+  return ORC_OK;
+}
+
 int orc_transfer_with_insert(orc_pool_t *src, orc_pool_t *dst, const uint32_t *tokens,
                              uint32_t n_tokens, uint32_t first_block,
                              const int32_t *src_blocks, int32_t *dst_blocks, uint32_t n,

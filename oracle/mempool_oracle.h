@@ -8,6 +8,8 @@
  * What is pinned, and to what (see tests/test_oracle_*.py):
  *   orc_gather / orc_scatter / orc_transfer : closed forms (permutation of an identity table,
  *       round-trip identity, untouched-block invariant), fragment counts of section 5.2.
+ *   orc_transfer_layers : numpy slicing closed form; layer ranges that tile [0,L) add up to
+ *       orc_transfer.
  *   orc_fnv1a64   : published FNV-1a-64 test vectors.
  *   orc_fmix64 / orc_chain_step : published splitmix64 outputs for seed 0.
  *   orc_block_hashes : composition of the two above, worked vectors under tests/golden/.
@@ -71,6 +73,8 @@ int orc_scatter(orc_pool_t *p, const int32_t *tbl, uint32_t n, const uint8_t *st
 
 int orc_transfer(orc_pool_t *src, orc_pool_t *dst, const int32_t *src_blocks,
                  int32_t *dst_blocks, uint32_t n, uint32_t flags);
+int orc_transfer_layers(orc_pool_t *src, orc_pool_t *dst, const int32_t *src_blocks,
+                        const int32_t *dst_blocks, uint32_t n, uint32_t l0, uint32_t l1);
 int orc_transfer_with_insert(orc_pool_t *src, orc_pool_t *dst, const uint32_t *tokens,
                              uint32_t n_tokens, uint32_t first_block,
                              const int32_t *src_blocks, int32_t *dst_blocks, uint32_t n,

@@ -56,6 +56,7 @@ def lib():
         L.orc_gather.argtypes = [vp, vp, C.c_uint32, vp]
         L.orc_scatter.argtypes = [vp, vp, C.c_uint32, vp]
         L.orc_transfer.argtypes = [vp, vp, vp, vp, C.c_uint32, C.c_uint32]
+        L.orc_transfer_layers.argtypes = [vp, vp, vp, vp, C.c_uint32, C.c_uint32, C.c_uint32]
         L.orc_transfer_with_insert.argtypes = [vp, vp, vp, C.c_uint32, C.c_uint32, vp, vp,
                                                C.c_uint32, C.c_uint32]
         L.orc_transfer_with_insert_batch.argtypes = [vp, vp, vp, vp, C.c_uint32, vp, vp, vp, vp,
@@ -180,6 +181,11 @@ def transfer(src: OraclePool, dst: OraclePool, src_blocks, dst_blocks=None, flag
     d = d.copy()
     rc = lib().orc_transfer(src.h, dst.h, _ptr(s), _ptr(d), s.size, flags)
     return rc, d
+
+
+def transfer_layers(src, dst, src_blocks, dst_blocks, l0, l1):
+    s, d = _i32(src_blocks), _i32(dst_blocks)
+    return lib().orc_transfer_layers(src.h, dst.h, _ptr(s), _ptr(d), s.size, l0, l1)
 
 
 def transfer_with_insert(src, dst, tokens, first_block, src_blocks, dst_blocks=None, flags=0):

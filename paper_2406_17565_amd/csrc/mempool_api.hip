@@ -46,12 +46,21 @@ struct DeviceCtx {
   int n_cus = 256;
   hipStream_t stream = nullptr;  // the caller's stream (from the pool descriptor)
   hipStream_t side = nullptr;    // library-owned, for pinned-host tier copies
-  MirrorBuf tables;              // [src ids][dst ids]
+  // Block tables go up through a small ring of pinned buffers so that asynchronous calls can
+  // run ahead of the GPU; the last uploaded pair is remembered, because by-layer transfers
+  // repeat one table pair for every layer.
+  static constexpr int kTableSlots = 4;
+  MirrorBuf tables[kTableSlots];  // each [src ids][dst ids]
+  hipEvent_t tables_uploaded[kTableSlots] = {nullptr, nullptr, nullptr, nullptr};
+  bool tables_pending[kTableSlots] = {false, false, false, false};
+  int tables_next = 0;
+  int tables_last = -1;           // slot holding `last_ids`, -1 = none
+  uint32_t last_n = 0;
+  bool last_has_src = false, last_has_dst = false;
+  std::vector<int32_t> last_ids;  // host copy of the last upload: [src n][dst n]
   MirrorBuf tokens;              // concatenated prompts
   MirrorBuf offsets;             // [tok_off][blk_off]
   MirrorBuf hashes;
-  hipEvent_t tables_uploaded = nullptr;
-  bool tables_pending = false;
   hipEvent_t slot_filled[2] = {nullptr, nullptr};   // main -> side (or side -> main)
   hipEvent_t slot_drained[2] = {nullptr, nullptr};  // the other direction
   bool slot_busy[2] = {false, false};
@@ -112,7 +121,8 @@ int ensure_device(mp_pool *p) {
   d.n_cus = cus > 0 ? cus : 256;
   d.stream = (hipStream_t)p->desc.stream;
   HIP_TRY(p, hipStreamCreateWithFlags(&d.side, hipStreamNonBlocking));
-  HIP_TRY(p, hipEventCreateWithFlags(&d.tables_uploaded, hipEventDisableTiming));
+  for (int s = 0; s < DeviceCtx::kTableSlots; ++s)
+    HIP_TRY(p, hipEventCreateWithFlags(&d.tables_uploaded[s], hipEventDisableTiming));
   for (int s = 0; s < 2; ++s) {
     HIP_TRY(p, hipEventCreateWithFlags(&d.slot_filled[s], hipEventDisableTiming));
     HIP_TRY(p, hipEventCreateWithFlags(&d.slot_drained[s], hipEventDisableTiming));
@@ -238,26 +248,43 @@ int device_hashes(mp_pool *p, const uint32_t *tokens, const uint32_t *tok_off, u
 int upload_tables(mp_pool *x, const int32_t *src_ids, const int32_t *dst_ids, uint32_t n,
                   const int32_t **d_src, const int32_t **d_dst) {
   DeviceCtx &d = x->dev;
-  int rc = reserve(x, d.tables, std::max<size_t>(8, 8ull * n));
-  if (rc != MP_OK) return rc;
-  if (d.tables_pending) {  // a previous asynchronous call may still be reading the pinned copy
-    HIP_TRY(x, hipEventSynchronize(d.tables_uploaded));
-    d.tables_pending = false;
+  // same pair as last time (every layer of a by-layer transfer): nothing to send
+  if (d.tables_last >= 0 && d.last_n == n && d.last_has_src == (src_ids != nullptr) &&
+      d.last_has_dst == (dst_ids != nullptr) &&
+      (!src_ids || std::memcmp(d.last_ids.data(), src_ids, 4ull * n) == 0) &&
+      (!dst_ids || std::memcmp(d.last_ids.data() + n, dst_ids, 4ull * n) == 0)) {
+    *d_src = (const int32_t *)d.tables[d.tables_last].dev;
+    *d_dst = (const int32_t *)d.tables[d.tables_last].dev + n;
+    return MP_OK;
   }
-  int32_t *h = (int32_t *)d.tables.host;
+  const int slot = d.tables_next;
+  d.tables_next = (slot + 1) % DeviceCtx::kTableSlots;
+  if (d.tables_last == slot) d.tables_last = -1;
+  if (d.tables_pending[slot]) {  // an earlier asynchronous call may still be reading this pinned copy
+    HIP_TRY(x, hipEventSynchronize(d.tables_uploaded[slot]));
+    d.tables_pending[slot] = false;
+  }
+  int rc = reserve(x, d.tables[slot], std::max<size_t>(8, 8ull * n));
+  if (rc != MP_OK) return rc;
+  int32_t *h = (int32_t *)d.tables[slot].host;
   if (src_ids) std::memcpy(h, src_ids, 4ull * n);
   if (dst_ids) std::memcpy(h + n, dst_ids, 4ull * n);
-  HIP_TRY(x, hipMemcpyAsync(d.tables.dev, h, 8ull * n, hipMemcpyHostToDevice, d.stream));
-  HIP_TRY(x, hipEventRecord(d.tables_uploaded, d.stream));
-  d.tables_pending = true;
-  *d_src = (const int32_t *)d.tables.dev;
-  *d_dst = (const int32_t *)d.tables.dev + n;
+  HIP_TRY(x, hipMemcpyAsync(d.tables[slot].dev, h, 8ull * n, hipMemcpyHostToDevice, d.stream));
+  HIP_TRY(x, hipEventRecord(d.tables_uploaded[slot], d.stream));
+  d.tables_pending[slot] = true;
+  d.last_ids.assign(h, h + 2ull * n);
+  d.last_n = n;
+  d.last_has_src = src_ids != nullptr;
+  d.last_has_dst = dst_ids != nullptr;
+  d.tables_last = slot;
+  *d_src = (const int32_t *)d.tables[slot].dev;
+  *d_dst = (const int32_t *)d.tables[slot].dev + n;
   return MP_OK;
 }
 
-CopySide pool_side(const mp_pool *p, const int32_t *d_tbl) {
+// `l0` = first layer addressed (by-layer transfers start in the middle of a block's planes).
+CopySide pool_side(const mp_pool *p, const int32_t *d_tbl, uint32_t l0 = 0) {
   CopySide s;
-  s.base = p->desc.base;
   s.tbl = d_tbl;
   if (p->desc.tier == MP_TIER_HBM) {  // discrete layout [L][2][NB][F]
     s.plane_stride = (uint64_t)p->desc.n_blocks * p->F;
@@ -266,15 +293,17 @@ CopySide pool_side(const mp_pool *p, const int32_t *d_tbl) {
     s.plane_stride = p->F;
     s.block_stride = p->B;
   }
+  s.base = (uint8_t *)p->desc.base + 2ull * l0 * s.plane_stride;
   return s;
 }
 
-CopySide record_side(const mp_pool *p, void *base) {
+// Records of `planes` fragments each, packed back to back (planes = 2*L for whole blocks).
+CopySide record_side(const mp_pool *p, void *base, uint32_t planes) {
   CopySide s;
   s.base = base;
   s.tbl = nullptr;
   s.plane_stride = p->F;
-  s.block_stride = p->B;
+  s.block_stride = (uint64_t)planes * p->F;
   return s;
 }
 
@@ -289,29 +318,36 @@ bool tables_overlap(const mp_pool *p, const int32_t *a, const int32_t *b, uint32
 }
 
 // Which staging problems would the copy hit?  Checked before any state changes.
-int check_copy_feasible(mp_pool *src, mp_pool *dst, uint32_t n, uint32_t flags) {
+int check_copy_feasible(mp_pool *src, mp_pool *dst, uint32_t n, uint32_t flags,
+                        uint32_t n_layers = 0 /* 0 = all */) {
   const bool s_hbm = src->desc.tier == MP_TIER_HBM, d_hbm = dst->desc.tier == MP_TIER_HBM;
   if (!s_hbm && !d_hbm) return fail(src, MP_ESHAPE, "host-to-host transfers are not supported");
   if (flags & MP_DIRECT) return MP_OK;  // no staging: the kernel addresses both pools itself
+  if (n_layers && (!s_hbm || !d_hbm))
+    return fail(src, MP_ESHAPE, "a by-layer transfer with a host-tier pool needs MP_DIRECT");
   if (n == 0) return MP_OK;
   mp_pool *x = s_hbm ? src : dst;
-  if (!x->desc.staging || x->desc.staging_bytes < x->B)
+  const uint64_t rec = n_layers ? 2ull * n_layers * x->F : x->B;
+  if (!x->desc.staging || x->desc.staging_bytes < rec)
     return fail(src, MP_ENOSTAGING, "staging buffer missing or smaller than one record");
   return MP_OK;
 }
 
 // The transmission step.  All ids are already validated.  Enqueues on the executing pool's
 // stream; the caller synchronises if it must.
+// Layers [l0, l1) of every block are moved (l1 = 0 means all layers).
 int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *dst_ids,
-             uint32_t n, uint32_t flags) {
+             uint32_t n, uint32_t flags, uint32_t l0 = 0, uint32_t l1 = 0) {
   if (n == 0) return MP_OK;
+  if (l1 == 0) l1 = src->desc.n_layers;
+  const uint32_t planes = 2 * (l1 - l0);
   const bool s_hbm = src->desc.tier == MP_TIER_HBM, d_hbm = dst->desc.tier == MP_TIER_HBM;
   mp_pool *x = s_hbm ? src : dst;  // the pool whose device context executes
   int rc = ensure_device(x);
   if (rc != MP_OK) return rc;
   DeviceCtx &d = x->dev;
   const CopyTune tune = effective_tune(x);
-  const uint64_t B = x->B;
+  const uint64_t B = (uint64_t)planes * x->F;  // bytes moved per table entry
   const int32_t *d_src = nullptr, *d_dst = nullptr;
   const bool direct = (flags & MP_DIRECT) != 0;
   rc = upload_tables(x, (s_hbm || direct) ? src_ids : nullptr, (d_hbm || direct) ? dst_ids : nullptr,
@@ -323,8 +359,8 @@ int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *
     // reads or writes host memory through the host link itself (zero-copy): no staging write,
     // no copy-engine hop.
     ProfScope ps(x, kProfDirect, 2ull * n * B);
-    HIP_TRY(x, launch_block_copy(pool_side(src, d_src), pool_side(dst, d_dst), n, x->P, x->F,
-                                 tune, d.n_cus, d.stream));
+    HIP_TRY(x, launch_block_copy(pool_side(src, d_src, l0), pool_side(dst, d_dst, l0), n, planes,
+                                 x->F, tune, d.n_cus, d.stream));
     return MP_OK;
   }
 
@@ -335,13 +371,15 @@ int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *
       const uint32_t cnt = std::min(cap, n - first);
       {
         ProfScope ps(x, kProfGather, 2ull * cnt * B);
-        HIP_TRY(x, launch_block_copy(pool_side(src, d_src + first), record_side(x, staging), cnt,
-                                     x->P, x->F, tune, d.n_cus, d.stream));
+        HIP_TRY(x, launch_block_copy(pool_side(src, d_src + first, l0),
+                                     record_side(x, staging, planes), cnt, planes, x->F, tune,
+                                     d.n_cus, d.stream));
       }
       {
         ProfScope ps(x, kProfScatter, 2ull * cnt * B);
-        HIP_TRY(x, launch_block_copy(record_side(x, staging), pool_side(dst, d_dst + first), cnt,
-                                     x->P, x->F, tune, d.n_cus, d.stream));
+        HIP_TRY(x, launch_block_copy(record_side(x, staging, planes),
+                                     pool_side(dst, d_dst + first, l0), cnt, planes, x->F, tune,
+                                     d.n_cus, d.stream));
       }
     }
     return MP_OK;
@@ -367,7 +405,7 @@ int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *
       if (d.slot_busy[s]) HIP_TRY(x, hipStreamWaitEvent(d.stream, d.slot_drained[s], 0));
       {
         ProfScope ps(x, kProfGather, 2ull * cnt * B);
-        HIP_TRY(x, launch_block_copy(pool_side(src, d_src + first), record_side(x, slot), cnt,
+        HIP_TRY(x, launch_block_copy(pool_side(src, d_src + first), record_side(x, slot, x->P), cnt,
                                      x->P, x->F, tune, d.n_cus, d.stream));
       }
       HIP_TRY(x, hipEventRecord(d.slot_filled[s], d.stream));
@@ -393,7 +431,7 @@ int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *
       HIP_TRY(x, hipStreamWaitEvent(d.stream, d.slot_filled[s], 0));
       {
         ProfScope ps(x, kProfScatter, 2ull * cnt * B);
-        HIP_TRY(x, launch_block_copy(record_side(x, slot), pool_side(dst, d_dst + first), cnt,
+        HIP_TRY(x, launch_block_copy(record_side(x, slot, x->P), pool_side(dst, d_dst + first), cnt,
                                      x->P, x->F, tune, d.n_cus, d.stream));
       }
       HIP_TRY(x, hipEventRecord(d.slot_drained[s], d.stream));
@@ -603,11 +641,11 @@ int mp_pool_destroy(mp_pool_t *p) {
     (void)hipStreamSynchronize(d.stream);
     (void)hipStreamSynchronize(d.side);
     prof_drain(p);
-    release(d.tables);
+    for (int s = 0; s < DeviceCtx::kTableSlots; ++s) release(d.tables[s]);
     release(d.tokens);
     release(d.offsets);
     release(d.hashes);
-    (void)hipEventDestroy(d.tables_uploaded);
+    for (int s = 0; s < DeviceCtx::kTableSlots; ++s) (void)hipEventDestroy(d.tables_uploaded[s]);
     for (int s = 0; s < 2; ++s) {
       (void)hipEventDestroy(d.slot_filled[s]);
       (void)hipEventDestroy(d.slot_drained[s]);
@@ -689,6 +727,25 @@ int mp_block_hashes(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, uin
   return MP_OK;
 }
 
+int mp_block_hashes_batch(mp_pool_t *p, const uint32_t *tokens, const uint32_t *tok_off,
+                          uint32_t n_req, uint64_t *out, uint32_t flags) {
+  if (!p) return MP_EINVAL;
+  if (!tok_off) return fail(p, MP_EINVAL, "null argument");
+  if (tok_off[0] != 0) return fail(p, MP_EINVAL, "offsets must start at 0");
+  for (uint32_t r = 0; r < n_req; ++r)
+    if (tok_off[r + 1] < tok_off[r]) return fail(p, MP_EINVAL, "offsets must be non-decreasing");
+  if (!tokens && tok_off[n_req]) return fail(p, MP_EINVAL, "null tokens");
+  std::vector<uint32_t> hoff;
+  const uint32_t *htok;
+  const uint64_t *hh;
+  int rc = device_hashes(p, tokens, tok_off, n_req, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok,
+                         &hh);
+  if (rc != MP_OK) return rc;
+  if (hoff[n_req] && !out) return fail(p, MP_EINVAL, "null output array");
+  std::memcpy(out, hh, 8ull * hoff[n_req]);
+  return MP_OK;
+}
+
 int mp_insert(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, const int32_t *blocks,
               uint32_t n_blocks, uint32_t flags, uint32_t *n_new_out) {
   if (!p) return MP_EINVAL;
@@ -765,6 +822,30 @@ int mp_transfer(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks, int32
   return MP_OK;
 }
 
+int mp_transfer_layers(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks,
+                       const int32_t *dst_blocks, uint32_t n, uint32_t layer_begin,
+                       uint32_t layer_end, uint32_t flags) {
+  if (!src || !dst) return MP_EINVAL;
+  if ((!src_blocks || !dst_blocks) && n) return fail(src, MP_EINVAL, "null block table");
+  if (!same_geometry(src, dst)) return fail(src, MP_ESHAPE, "source and destination geometry differ");
+  if (layer_begin >= layer_end || layer_end > src->desc.n_layers)
+    return fail(src, MP_EINVAL, "layer range must be non-empty and inside [0, n_layers]");
+  int rc = check_src_ids(src, src_blocks, n);
+  if (rc != MP_OK) return rc;
+  if (!dst->idx.held_and_distinct(dst_blocks, n))
+    return fail(src, MP_EINVAL, "destination ids must be held and distinct");
+  if ((rc = check_copy_feasible(src, dst, n, flags, layer_end - layer_begin)) != MP_OK) return rc;
+  if (src == dst && n && tables_overlap(src, src_blocks, dst_blocks, n)) {
+    if (flags & MP_DIRECT)
+      return fail(src, MP_EINVAL, "MP_DIRECT within one pool needs disjoint tables");
+    if ((uint64_t)n * 2ull * (layer_end - layer_begin) * src->F > src->desc.staging_bytes)
+      return fail(src, MP_ENOSTAGING, "overlapping in-pool transfer must fit the staging buffer");
+  }
+  rc = run_copy(src, dst, src_blocks, dst_blocks, n, flags, layer_begin, layer_end);
+  if (rc == MP_OK) rc = finish_copy(src, dst, flags);
+  return rc;
+}
+
 int mp_transfer_with_insert(mp_pool_t *src, mp_pool_t *dst, const uint32_t *tokens,
                             uint32_t n_tokens, uint32_t first_block, const int32_t *src_blocks,
                             int32_t *dst_blocks, uint32_t n, uint32_t flags, const void *priv,
@@ -799,7 +880,7 @@ int mp_gather(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags) {
   if ((rc = upload_tables(p, tbl, nullptr, n, &d_src, &d_dst)) != MP_OK) return rc;
   {
     ProfScope ps(p, kProfGather, 2ull * n * p->B);
-    HIP_TRY(p, launch_block_copy(pool_side(p, d_src), record_side(p, p->desc.staging), n, p->P,
+    HIP_TRY(p, launch_block_copy(pool_side(p, d_src), record_side(p, p->desc.staging, p->P), n, p->P,
                                  p->F, effective_tune(p), p->dev.n_cus, p->dev.stream));
   }
   if (!(flags & MP_ASYNC)) HIP_TRY(p, hipStreamSynchronize(p->dev.stream));
@@ -825,7 +906,7 @@ int mp_scatter(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags) {
   if ((rc = upload_tables(p, nullptr, tbl, n, &d_src, &d_dst)) != MP_OK) return rc;
   {
     ProfScope ps(p, kProfScatter, 2ull * n * p->B);
-    HIP_TRY(p, launch_block_copy(record_side(p, p->desc.staging), pool_side(p, d_dst), n, p->P,
+    HIP_TRY(p, launch_block_copy(record_side(p, p->desc.staging, p->P), pool_side(p, d_dst), n, p->P,
                                  p->F, effective_tune(p), p->dev.n_cus, p->dev.stream));
   }
   if (!(flags & MP_ASYNC)) HIP_TRY(p, hipStreamSynchronize(p->dev.stream));

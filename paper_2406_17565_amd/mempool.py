@@ -24,7 +24,8 @@ EXPORTS = [
     "mp_transfer_with_insert", "mp_match_batch", "mp_transfer_with_insert_batch",
     "mp_block_hashes", "mp_insert_hashed", "mp_match_hashed", "mp_gather", "mp_scatter",
     "mp_set_recv_callback", "mp_profile_enable", "mp_profile_read", "mp_set_tunable",
-    "mp_selftest", "mp_plain_copy",
+    "mp_selftest", "mp_plain_copy", "mp_transfer_layers",
+    "mp_block_hashes_batch",
 ]
 
 
@@ -69,9 +70,11 @@ def lib():
             "mp_evict": [vp, u32, C.POINTER(u32)],
             "mp_transfer": [vp, vp, vp, vp, u32, u32, vp, u64],
             "mp_transfer_with_insert": [vp, vp, vp, u32, u32, vp, vp, u32, u32, vp, u64],
+            "mp_transfer_layers": [vp, vp, vp, vp, u32, u32, u32, u32],
             "mp_match_batch": [vp, vp, vp, u32, vp, vp, vp, u32],
             "mp_transfer_with_insert_batch": [vp, vp, vp, vp, u32, vp, vp, vp, vp, u32],
             "mp_block_hashes": [vp, vp, u32, vp, u32],
+            "mp_block_hashes_batch": [vp, vp, vp, u32, vp, u32],
             "mp_insert_hashed": [vp, vp, u32, vp, vp, u32, u32, C.POINTER(u32)],
             "mp_match_hashed": [vp, vp, u32, vp, vp, u32, C.POINTER(u32), u32],
             "mp_gather": [vp, vp, u32, u32],
@@ -189,6 +192,12 @@ def mp_transfer(src, dst, src_blocks, dst_blocks=None, flags=0, priv=b""):
     return rc, d
 
 
+def mp_transfer_layers(src, dst, src_blocks, dst_blocks, layer_begin, layer_end, flags=0):
+    s, d = _i32(src_blocks), _i32(dst_blocks)
+    assert s.size == d.size
+    return lib().mp_transfer_layers(src, dst, _ptr(s), _ptr(d), s.size, layer_begin, layer_end, flags)
+
+
 def mp_transfer_with_insert(src, dst, tokens, first_block, src_blocks, dst_blocks=None, flags=0,
                             priv=b"", n_tokens=None):
     tp, nt, keep = _tok(tokens, n_tokens)
@@ -226,6 +235,17 @@ def mp_block_hashes(p, tokens, block_size, flags=0, n_tokens=None):
     out = np.zeros(nt // block_size, dtype=np.uint64)
     rc = lib().mp_block_hashes(p, tp, nt, _ptr(out), flags)
     return rc, out
+
+
+def mp_block_hashes_batch(p, tokens, tok_off, block_size, flags=0):
+    """Returns (rc, hashes of all prompts back to back, hash offsets[n_req+1])."""
+    to = _u32(tok_off)
+    tp, nt, keep = _tok(tokens, int(to[-1]))
+    nb = (to[1:] - to[:-1]) // block_size
+    hoff = np.concatenate([[0], np.cumsum(nb)]).astype(np.uint32)
+    out = np.zeros(int(hoff[-1]), dtype=np.uint64)
+    rc = lib().mp_block_hashes_batch(p, tp, to.ctypes.data, to.size - 1, _ptr(out), flags)
+    return rc, out, hoff
 
 
 def mp_insert_hashed(p, tokens, hashes, blocks, flags=0):

@@ -63,6 +63,21 @@ def test_block_hashes(gpu, bs):
         p.close()
 
 
+def test_block_hashes_batch(gpu):
+    M, TorchPool = gpu
+    bs = 16
+    rng = np.random.default_rng(77)
+    p = TorchPool(1, 1, 8, bs, 2, 4, seed=5)
+    prompts = [rng.integers(0, 2**32, int(n), dtype=np.uint32)
+               for n in (0, 5, 16, 700, 16 * 1030 + 9, 31, 4096)]
+    toks, tok_off = W.csr(prompts)
+    rc, h, hoff = M.mp_block_hashes_batch(p.h, toks, tok_off, bs)
+    assert rc == 0
+    for r, t in enumerate(prompts):
+        assert np.array_equal(h[hoff[r]:hoff[r + 1]], O.block_hashes(t, bs, 5))
+    p.close()
+
+
 def test_block_hashes_golden(gpu, golden_dir):
     M, TorchPool = gpu
     import os
@@ -452,3 +467,45 @@ def test_profile_counters(gpu):
     assert M.mp_profile_read(sg.h, M.PROF_GATHER)[2] == 0      # cleared by the read
     sg.close()
     dg.close()
+
+
+@pytest.mark.parametrize("mode", ["staged", "rounds", "direct"])
+def test_transfer_layers(gpu, mode):
+    """By-layer transfer: explicit destinations, a layer range per call."""
+    M, TorchPool = gpu
+    geom = (5, 2, 64, 16, 2)                     # L = 5, F = 4 KiB
+    flags = M.MP_DIRECT if mode == "direct" else 0
+    so, sg = make_pair(gpu, geom, 40, 4, staging_blocks=2 if mode == "rounds" else 16)
+    do, dg = make_pair(gpu, geom, 30, 5, staging_blocks=0)
+    M.mp_alloc(sg.h, 40)
+    so.alloc(40)
+    rng = np.random.default_rng(6)
+    tbl = rng.integers(0, 40, 13).astype(np.int32)
+    rc, d = M.mp_alloc(dg.h, 13)
+    rco, d_o = do.alloc(13)
+    assert rc == rco == 0 and d.tolist() == d_o.tolist()
+    for l0, l1 in ((0, 1), (1, 2), (2, 5)):       # the engine ships layers as they finish
+        assert M.mp_transfer_layers(sg.h, dg.h, tbl, d, l0, l1, flags) == 0, M.mp_last_error(sg.h)
+        assert O.transfer_layers(so, do, tbl, d_o, l0, l1) == 0
+        _same_state(do, dg)
+    # after the last layer the destination equals a whole-block transfer
+    ref = O.OraclePool(*geom, 30, data=make_pair(gpu, geom, 30, 5, 0)[0].data)
+    ref.alloc(13)
+    assert O.transfer(so, ref, tbl, d_o, flags=O.DST_GIVEN)[0] == 0
+    assert np.array_equal(dg.bytes(), ref.data)
+    snap = dg.bytes()
+    assert M.mp_transfer_layers(sg.h, dg.h, tbl, d, 2, 2, flags) == M.MP_EINVAL
+    assert M.mp_transfer_layers(sg.h, dg.h, tbl, d, 3, 6, flags) == M.MP_EINVAL
+    assert M.mp_transfer_layers(sg.h, dg.h, tbl[:2], [29, 28], 0, 1, flags) == M.MP_EINVAL   # not held
+    assert M.mp_transfer_layers(sg.h, dg.h, tbl[:2], [d[0], d[0]], 0, 1, flags) == M.MP_EINVAL
+    assert np.array_equal(dg.bytes(), snap)
+    # host tier: only through the fused kernel
+    ho, hg = make_pair(gpu, geom, 16, 8, staging_blocks=0, tier=1)
+    rc, h = M.mp_alloc(hg.h, 13)
+    ho.alloc(13)
+    assert M.mp_transfer_layers(sg.h, hg.h, tbl, h, 1, 4, 0) == M.MP_ESHAPE
+    assert M.mp_transfer_layers(sg.h, hg.h, tbl, h, 1, 4, M.MP_DIRECT) == 0
+    assert O.transfer_layers(so, ho, tbl, h, 1, 4) == 0
+    _same_state(ho, hg)
+    for p in (sg, dg, hg):
+        p.close()

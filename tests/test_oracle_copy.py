@@ -144,3 +144,37 @@ def test_transfer_within_one_pool_reads_everything_before_writing():
     b = before.reshape(6, p.B)
     assert np.array_equal(after[1], b[0]) and np.array_equal(after[2], b[1])
     assert np.array_equal(after[0], b[2]) and np.array_equal(after[3:], b[3:])
+
+
+def test_transfer_layers_is_a_slice_of_the_transfer():
+    geom = (5, 2, 8, 4, 2)                       # L = 5
+    L = geom[0]
+    rng = np.random.default_rng(21)
+    s_ids, d_ids = [7, 2, 7, 9], [3, 0, 5, 1]
+    for l0, l1 in ((0, 1), (2, 5), (1, 3), (0, 5)):
+        src, dst = _pool(geom, 12, 20), _pool(geom, 8, 21)
+        src.alloc(12)
+        dst.alloc(6)
+        before = dst.data.copy().reshape(L, 2, 8, dst.F)
+        assert O.transfer_layers(src, dst, s_ids, d_ids, l0, l1) == 0
+        after = dst.data.reshape(L, 2, 8, dst.F)
+        s4 = src.data.reshape(L, 2, 12, src.F)
+        assert np.array_equal(after[l0:l1][:, :, d_ids], s4[l0:l1][:, :, s_ids])
+        mask = np.ones((L, 2, 8), bool)
+        mask[l0:l1, :, d_ids] = False
+        assert np.array_equal(after[mask], before[mask])          # other layers / blocks untouched
+    # ranges that tile [0, L) add up to the whole-block transfer
+    src, a, b = _pool(geom, 12, 20), _pool(geom, 8, 21), _pool(geom, 8, 21)
+    src.alloc(12)
+    a.alloc(6)
+    b.alloc(6)
+    for l0, l1 in ((3, 5), (0, 2), (2, 3)):
+        assert O.transfer_layers(src, a, s_ids, d_ids, l0, l1) == 0
+    assert O.transfer(src, b, s_ids, d_ids, flags=O.DST_GIVEN)[0] == 0
+    assert np.array_equal(a.data, b.data)
+    # errors
+    assert O.transfer_layers(src, a, s_ids, d_ids, 2, 2) == O.EINVAL
+    assert O.transfer_layers(src, a, s_ids, d_ids, 4, 6) == O.EINVAL
+    assert O.transfer_layers(src, a, s_ids, [3, 3, 5, 1], 0, 1) == O.EINVAL
+    assert O.transfer_layers(src, a, s_ids, [3, 0, 5, 7], 0, 1) == O.EINVAL   # 7 not held
+    assert np.array_equal(a.data, b.data)
