@@ -204,6 +204,69 @@ def host_tier(args):
     host.close()
 
 
+def api_latency(args):
+    """Latency of the control-plane calls, next to the paper's API study (section 8.4: about
+    800 ns per block for the memory APIs, at most 0.7 ms to insert a 4K-token prompt of 256
+    blocks, on the authors' Xeon host in Python)."""
+    import torch
+    from paper_2406_17565_amd import mempool as M
+    from paper_2406_17565_amd import workloads as W
+    from paper_2406_17565_amd.pool import TorchPool
+    g = W.CONFIGS[3]
+    p = TorchPool(1, 1, 8, g.bs, 2, g.NB)      # the control plane does not depend on fragment size
+    rng = np.random.default_rng(0)
+
+    def best(f, reps=30):
+        ts = []
+        for _ in range(reps):
+            t0 = time.perf_counter()
+            f()
+            ts.append(time.perf_counter() - t0)
+        return min(ts)
+
+    out = {"metric": "MemPool API latency", "unit": "us", "n_gpus": 1, "data": "synthetic",
+           "paper_context": {"alloc_free_ns_per_block": 800, "insert_256_blocks_ms": 0.7}}
+    for n in (16, 256, 4096):
+        def alloc_free():
+            rc, ids = M.mp_alloc(p.h, n)
+            M.mp_free(p.h, ids)
+        out[f"alloc+free_{n}_blocks_ns_per_block"] = round(best(alloc_free) / n * 1e9, 1)
+    prompt = rng.integers(0, g.vocab, 256 * g.bs, dtype=np.uint32)      # 4K tokens = 256 blocks
+    rc, ids = M.mp_alloc(p.h, 256)
+    rc, hashes = M.mp_block_hashes(p.h, prompt, g.bs)
+    out["block_hashes_256_blocks_us"] = round(best(lambda: M.mp_block_hashes(p.h, prompt, g.bs)) * 1e6, 1)
+    for cached in (0, 128, 256):                 # cached ratio 0 %, 50 %, 100 %
+        ts_i, ts_m = [], []
+        for _ in range(20):
+            # rebuild the state: nothing indexed, `ids` held, first `cached` blocks inserted
+            M.mp_free(p.h, ids); M.mp_evict(p.h, 4096); rc, ids = M.mp_alloc(p.h, 256)
+            if cached:
+                M.mp_insert_hashed(p.h, prompt[: cached * g.bs], hashes[:cached], ids[:cached])
+            t0 = time.perf_counter()
+            rc, n_new = M.mp_insert_hashed(p.h, prompt, hashes, ids)
+            ts_i.append(time.perf_counter() - t0)
+            assert rc == 0 and n_new == 256 - cached
+            t0 = time.perf_counter()
+            rc, m = M.mp_match_hashed(p.h, prompt, hashes, 256)
+            ts_m.append(time.perf_counter() - t0)
+            assert len(m) == 256
+        out[f"insert_hashed_256_blocks_cached{cached}_us"] = round(min(ts_i) * 1e6, 1)
+        out[f"match_hashed_256_blocks_cached{cached}_us"] = round(min(ts_m) * 1e6, 1)
+    out["match_256_blocks_end_to_end_us"] = round(best(lambda: M.mp_match(p.h, prompt, 256)) * 1e6, 1)
+    M.mp_free(p.h, ids); M.mp_evict(p.h, 4096); rc, ids = M.mp_alloc(p.h, 256)
+
+    def ins():
+        M.mp_insert(p.h, prompt, ids)
+    out["insert_256_blocks_end_to_end_us"] = round(best(ins) * 1e6, 1)
+    turn = build_epoch(W, g, 3, 0)[3]             # 64 prompts of about 2K tokens
+    nb = int(((turn["tok_off"][1:] - turn["tok_off"][:-1]) // g.bs).sum())
+    t = best(lambda: M.mp_match_batch(p.h, turn["toks"], turn["tok_off"], turn["cap_off"]), 20)
+    out["match_batch_64_prompts_us"] = round(t * 1e6, 1)
+    out["match_batch_blocks_per_s"] = round(nb / t, 1)
+    print(json.dumps(out))
+    p.close()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -215,6 +278,7 @@ def main():
     ap.add_argument("--by-layer", action="store_true",
                     help="ship one layer per call (mp_transfer_layers) instead of whole blocks")
     ap.add_argument("--host-tier", action="store_true", help="config 5 HBM <-> pinned-host variant")
+    ap.add_argument("--api-latency", action="store_true", help="latency of the control-plane calls")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tune", default="", help="comma list key=value for mp_set_tunable")
     args = ap.parse_args()
@@ -225,6 +289,8 @@ def main():
 
     if args.host_tier:
         return host_tier(args)
+    if args.api_latency:
+        return api_latency(args)
     if args.steps is None:
         args.steps = {2: 8, 3: 20, 4: 32, 5: 6}[args.config]
     if args.warmup is None:

@@ -122,6 +122,13 @@ int mp_insert(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, const int
 int mp_match(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, int32_t *blocks_out,
              uint32_t cap, uint32_t *n_matched_out, uint32_t flags);
 
+/* delete (Table 1): delete the prompt's cached data, if any.  Walking up from the deepest
+ * indexed block of the prompt, every node that is an unreferenced leaf is removed and its
+ * block freed (deepest first); the walk stops at the first node that other prompts share
+ * (it has other children) or that is referenced.  *n_deleted_out = blocks freed. */
+int mp_delete(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, uint32_t flags,
+              uint32_t *n_deleted_out);
+
 /* evict (Table 3): up to n_blocks times, free the least recently used unreferenced LEAF of the
  * index (ties: smallest block id).  *n_evicted_out may be smaller than n_blocks. */
 int mp_evict(mp_pool_t *p, uint32_t n_blocks, uint32_t *n_evicted_out);
@@ -192,6 +199,8 @@ int mp_insert_hashed(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens,
 int mp_match_hashed(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens,
                     const uint64_t *hashes, int32_t *blocks_out, uint32_t cap,
                     uint32_t *n_matched_out, uint32_t flags);
+int mp_delete_hashed(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens,
+                     const uint64_t *hashes, uint32_t *n_deleted_out);
 
 /* Data-plane pieces of a transfer, exposed for tests and measurement.  `tbl` are HOST arrays
  * of n block ids; `staging` of the pool is the other end. */

@@ -336,6 +336,27 @@ int orc_match(orc_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, int32_t 
   return ORC_OK;
 }
 
+// delete (Table 1: "delete prompt's cached data if any").  The paper says no more; reading:
+// the prompt's own blocks go, shared or referenced ones stay -- from the deepest matched node
+// upwards, remove nodes while they are unreferenced leaves.
+int orc_delete(orc_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, uint32_t *n_deleted) {
+  if (!p || (!tokens && n_tokens) || !n_deleted) return ORC_EINVAL;
+  std::vector<Node *> path = walk(p, tokens, n_tokens / p->bs);
+  uint32_t done = 0;
+  while (!path.empty()) {
+    Node *n = path.back();
+    if (!n->children.empty() || p->ref[n->block] != 0) break;
+    path.pop_back();
+    n->parent->children.erase(n->key);
+    p->node_of[n->block] = nullptr;
+    p->free_stack.push_back(n->block);
+    delete n;
+    ++done;
+  }
+  *n_deleted = done;
+  return ORC_OK;
+}
+
 int orc_evict(orc_pool_t *p, uint32_t k, uint32_t *n_evicted) {
   if (!p || !n_evicted) return ORC_EINVAL;
   uint32_t done = 0;

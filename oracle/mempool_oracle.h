@@ -14,7 +14,7 @@
  *   orc_fmix64 / orc_chain_step : published splitmix64 outputs for seed 0.
  *   orc_block_hashes : composition of the two above, worked vectors under tests/golden/.
  *   orc_match / orc_insert : brute-force longest common block-aligned prefix on tiny inputs.
- *   orc_evict, orc_alloc / orc_free : scripted scenarios derived by hand from the rule.
+ *   orc_evict, orc_delete, orc_alloc / orc_free : scripted scenarios derived by hand from the rule.
  *   PARITY UNPINNED against the paper: the paper fixes neither a hash function, nor the
  *   allocation order, nor an eviction policy; those three are conventions of this build
  *   and are pinned only to their own written definitions.
@@ -66,6 +66,7 @@ int orc_insert(orc_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, const i
 int orc_match(orc_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, int32_t *blocks_out,
               uint32_t cap, uint32_t *n_matched, uint32_t flags);
 int orc_evict(orc_pool_t *p, uint32_t k, uint32_t *n_evicted);
+int orc_delete(orc_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, uint32_t *n_deleted);
 
 /* copy by block table; staging is [n][L][2][F] */
 int orc_gather(const orc_pool_t *p, const int32_t *tbl, uint32_t n, uint8_t *staging);

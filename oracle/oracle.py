@@ -53,6 +53,7 @@ def lib():
         L.orc_insert.argtypes = [vp, vp, C.c_uint32, vp, C.c_uint32, u32p]
         L.orc_match.argtypes = [vp, vp, C.c_uint32, vp, C.c_uint32, u32p, C.c_uint32]
         L.orc_evict.argtypes = [vp, C.c_uint32, u32p]
+        L.orc_delete.argtypes = [vp, vp, C.c_uint32, u32p]
         L.orc_gather.argtypes = [vp, vp, C.c_uint32, vp]
         L.orc_scatter.argtypes = [vp, vp, C.c_uint32, vp]
         L.orc_transfer.argtypes = [vp, vp, vp, vp, C.c_uint32, C.c_uint32]
@@ -157,6 +158,12 @@ class OraclePool:
         m = C.c_uint32(0)
         rc = lib().orc_match(self.h, _ptr(t), t.size, _ptr(out), cap, C.byref(m), flags)
         return rc, out[: m.value].copy()
+
+    def delete(self, tokens):
+        t = _u32(tokens)
+        n = C.c_uint32(0)
+        rc = lib().orc_delete(self.h, _ptr(t), t.size, C.byref(n))
+        return rc, n.value
 
     def evict(self, k):
         n = C.c_uint32(0)

@@ -131,7 +131,7 @@ int ensure_device(mp_pool *p) {
   return MP_OK;
 }
 
-int reserve(mp_pool *p, MirrorBuf &b, size_t bytes) {
+int reserve(mp_pool *p, MirrorBuf &b, size_t bytes, bool need_dev = true) {
   if (bytes <= b.cap) return MP_OK;
   size_t cap = b.cap ? b.cap : 4096;
   while (cap < bytes) cap *= 2;
@@ -141,7 +141,7 @@ int reserve(mp_pool *p, MirrorBuf &b, size_t bytes) {
   if (b.host) HIP_TRY(p, hipHostFree(b.host));
   b.dev = b.host = nullptr;
   b.cap = 0;
-  HIP_TRY(p, hipMalloc(&b.dev, cap));
+  if (need_dev) HIP_TRY(p, hipMalloc(&b.dev, cap));
   HIP_TRY(p, hipHostMalloc(&b.host, cap, hipHostMallocDefault));
   b.cap = cap;
   return MP_OK;
@@ -193,7 +193,7 @@ void prof_drain(mp_pool *p) {
 
 // ---- hashing through the device kernel ------------------------------------------------------
 // Computes the chained hashes of n_req prompts into p->dev.hashes.host; blk_off_out receives
-// the n_req+1 offsets into that array.  Host tokens are staged through pinned memory; device
+// the n_req+1 offsets into that array.  Host tokens are copied into pinned memory; device
 // tokens are also copied back, because index nodes keep (and compare) their tokens.
 // On return *host_tokens points at a host copy of all tokens.
 int device_hashes(mp_pool *p, const uint32_t *tokens, const uint32_t *tok_off, uint32_t n_req,
@@ -208,37 +208,33 @@ int device_hashes(mp_pool *p, const uint32_t *tokens, const uint32_t *tok_off, u
   for (uint32_t r = 0; r < n_req; ++r)
     blk_off_out[r + 1] = blk_off_out[r] + (tok_off[r + 1] - tok_off[r]) / bs;
   const uint32_t total_blk = blk_off_out[n_req];
-  if ((rc = reserve(p, d.tokens, std::max<size_t>(4, 4ull * total_tok))) != MP_OK) return rc;
-  if ((rc = reserve(p, d.offsets, 8ull * (n_req + 1))) != MP_OK) return rc;
-  if ((rc = reserve(p, d.hashes, std::max<size_t>(8, 8ull * total_blk))) != MP_OK) return rc;
+  if ((rc = reserve(p, d.tokens, std::max<size_t>(4, 4ull * total_tok), false)) != MP_OK) return rc;
+  if ((rc = reserve(p, d.offsets, 8ull * (n_req + 1), false)) != MP_OK) return rc;
+  if ((rc = reserve(p, d.hashes, std::max<size_t>(8, 8ull * total_blk), false)) != MP_OK) return rc;
   *host_tokens = on_device ? (const uint32_t *)d.tokens.host : tokens;
   *host_hashes = (const uint64_t *)d.hashes.host;
   if (total_blk == 0) return MP_OK;
 
+  // Offsets, host tokens and the hashes live in pinned host memory that the kernel addresses
+  // directly (zero-copy): a match costs one kernel launch and one stream synchronisation,
+  // no copy-engine commands.  The volumes are tiny (4 B per token in, 8 B per block out).
   uint32_t *h_off = (uint32_t *)d.offsets.host;
   std::memcpy(h_off, tok_off, 4ull * (n_req + 1));
   std::memcpy(h_off + n_req + 1, blk_off_out.data(), 4ull * (n_req + 1));
-  HIP_TRY(p, hipMemcpyAsync(d.offsets.dev, h_off, 8ull * (n_req + 1), hipMemcpyHostToDevice,
-                            d.stream));
-  const uint32_t *d_tok;
+  const uint32_t *k_tok;
   if (on_device) {
-    d_tok = tokens;
+    k_tok = tokens;
     HIP_TRY(p, hipMemcpyAsync(d.tokens.host, tokens, 4ull * total_tok, hipMemcpyDeviceToHost,
                               d.stream));
   } else {
     std::memcpy(d.tokens.host, tokens, 4ull * total_tok);
-    HIP_TRY(p, hipMemcpyAsync(d.tokens.dev, d.tokens.host, 4ull * total_tok,
-                              hipMemcpyHostToDevice, d.stream));
-    d_tok = (const uint32_t *)d.tokens.dev;
+    k_tok = (const uint32_t *)d.tokens.host;
   }
   {
     ProfScope ps(p, kProfHash, 4ull * bs * total_blk + 8ull * total_blk);
-    const uint32_t *d_off = (const uint32_t *)d.offsets.dev;
-    HIP_TRY(p, launch_block_hash(d_tok, d_off, d_off + n_req + 1, n_req, bs, p->desc.hash_seed,
-                                 (uint64_t *)d.hashes.dev, d.stream));
+    HIP_TRY(p, launch_block_hash(k_tok, h_off, h_off + n_req + 1, n_req, bs, p->desc.hash_seed,
+                                 (uint64_t *)d.hashes.host, d.stream));
   }
-  HIP_TRY(p, hipMemcpyAsync(d.hashes.host, d.hashes.dev, 8ull * total_blk, hipMemcpyDeviceToHost,
-                            d.stream));
   HIP_TRY(p, hipStreamSynchronize(d.stream));
   return MP_OK;
 }
@@ -792,6 +788,32 @@ int mp_match(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, int32_t *b
   if (!n_matched_out) return fail(p, MP_EINVAL, "null argument");
   const uint32_t tok_off[2] = {0, n_tokens}, blk_off[2] = {0, cap};
   return mp_match_batch(p, tokens, tok_off, 1, blocks_out, blk_off, n_matched_out, flags);
+}
+
+int mp_delete_hashed(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens,
+                     const uint64_t *hashes, uint32_t *n_deleted_out) {
+  if (!p) return MP_EINVAL;
+  if ((!tokens && n_tokens) || !n_deleted_out) return fail(p, MP_EINVAL, "null argument");
+  const uint32_t nb = n_tokens / p->desc.block_size;
+  if (!hashes && nb) return fail(p, MP_EINVAL, "null hashes");
+  std::vector<int32_t> &path = p->scratch_ids;
+  path.resize(nb);
+  const uint32_t m = p->idx.walk(tokens, hashes, nb, path.data());
+  *n_deleted_out = p->idx.erase_path(path.data(), m);
+  return MP_OK;
+}
+
+int mp_delete(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, uint32_t flags,
+              uint32_t *n_deleted_out) {
+  if (!p) return MP_EINVAL;
+  if ((!tokens && n_tokens) || !n_deleted_out) return fail(p, MP_EINVAL, "null argument");
+  const uint32_t tok_off[2] = {0, n_tokens};
+  std::vector<uint32_t> hoff;
+  const uint32_t *htok;
+  const uint64_t *hh;
+  int rc = device_hashes(p, tokens, tok_off, 1, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok, &hh);
+  if (rc != MP_OK) return rc;
+  return mp_delete_hashed(p, htok, n_tokens, hh, n_deleted_out);
 }
 
 int mp_evict(mp_pool_t *p, uint32_t n_blocks, uint32_t *n_evicted_out) {

@@ -293,6 +293,33 @@ class PoolIndex {
     return done;
   }
 
+  // delete: drop the prompt's own cached blocks -- from the deepest matched node upwards,
+  // every node that is an unreferenced leaf; stops at the first node that is shared (has other
+  // children) or referenced.  `path` = the matched blocks, root side first.
+  uint32_t erase_path(const int32_t *path, uint32_t m) {
+    uint32_t done = 0;
+    for (uint32_t i = m; i-- > 0;) {
+      const int32_t b = path[i];
+      if (n_children_[b] != 0 || ref_[b] != 0) break;
+      if (in_lru_[b]) {
+        lru_.erase({lru_key_[b], b});
+        in_lru_[b] = 0;
+      }
+      table_.erase(hash_[b]);
+      indexed_[b] = 0;
+      --n_indexed_;
+      const int32_t par = parent_[b];
+      parent_[b] = kNoBlock;
+      if (par != kNoBlock) {
+        --n_children_[par];
+        refresh_lru(par);
+      }
+      free_.push_back(b);
+      ++done;
+    }
+    return done;
+  }
+
   uint32_t node_instance(int32_t b) const { return node_instance_[b]; }
   uint32_t node_tier(int32_t b) const { return node_tier_[b]; }
 

@@ -25,7 +25,7 @@ EXPORTS = [
     "mp_block_hashes", "mp_insert_hashed", "mp_match_hashed", "mp_gather", "mp_scatter",
     "mp_set_recv_callback", "mp_profile_enable", "mp_profile_read", "mp_set_tunable",
     "mp_selftest", "mp_plain_copy", "mp_transfer_layers",
-    "mp_block_hashes_batch",
+    "mp_block_hashes_batch", "mp_delete", "mp_delete_hashed",
 ]
 
 
@@ -68,6 +68,8 @@ def lib():
             "mp_insert": [vp, vp, u32, vp, u32, u32, C.POINTER(u32)],
             "mp_match": [vp, vp, u32, vp, u32, C.POINTER(u32), u32],
             "mp_evict": [vp, u32, C.POINTER(u32)],
+            "mp_delete": [vp, vp, u32, u32, C.POINTER(u32)],
+            "mp_delete_hashed": [vp, vp, u32, vp, C.POINTER(u32)],
             "mp_transfer": [vp, vp, vp, vp, u32, u32, vp, u64],
             "mp_transfer_with_insert": [vp, vp, vp, u32, u32, vp, vp, u32, u32, vp, u64],
             "mp_transfer_layers": [vp, vp, vp, vp, u32, u32, u32, u32],
@@ -177,6 +179,21 @@ def mp_match(p, tokens, cap, flags=0, n_tokens=None):
     m = C.c_uint32(0)
     rc = lib().mp_match(p, tp, nt, _ptr(out), cap, C.byref(m), flags)
     return rc, out[: m.value].copy()
+
+
+def mp_delete(p, tokens, flags=0, n_tokens=None):
+    tp, nt, keep = _tok(tokens, n_tokens)
+    n = C.c_uint32(0)
+    rc = lib().mp_delete(p, tp, nt, flags, C.byref(n))
+    return rc, n.value
+
+
+def mp_delete_hashed(p, tokens, hashes):
+    t = _u32(tokens)
+    h = np.ascontiguousarray(hashes, dtype=np.uint64)
+    n = C.c_uint32(0)
+    rc = lib().mp_delete_hashed(p, _ptr(t), t.size, _ptr(h), C.byref(n))
+    return rc, n.value
 
 
 def mp_evict(p, n_blocks):

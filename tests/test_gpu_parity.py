@@ -298,6 +298,9 @@ def test_random_workflow_against_oracle(gpu, seed):
         if rng.integers(0, 5) == 0:
             k = int(rng.integers(0, 4))
             assert M.mp_evict(dg.h, k) == do.evict(k)
+        if prompts and rng.integers(0, 6) == 0:
+            t = prompts[int(rng.integers(0, len(prompts)))]
+            assert M.mp_delete(dg.h, t) == do.delete(t)
         _same_state(do, dg)
     sg.close()
     dg.close()

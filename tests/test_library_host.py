@@ -65,7 +65,7 @@ def test_random_sequences_match_the_oracle(seed):
     held = []          # ids we hold one reference on (same on both sides)
     prompts = []
     for step in range(400):
-        op = rng.integers(0, 6)
+        op = rng.integers(0, 7)
         if op == 0:      # alloc
             n = int(rng.integers(0, 6))
             fl = M.MP_EVICT_ON_DEMAND if rng.integers(0, 2) else 0
@@ -118,6 +118,10 @@ def test_random_sequences_match_the_oracle(seed):
         elif op == 4:    # evict
             k = int(rng.integers(0, 4))
             assert M.mp_evict(p.g, k) == p.o.evict(k)
+        elif op == 5 and prompts:   # delete a stored prompt (or a prefix / extension of one)
+            base = prompts[int(rng.integers(0, len(prompts)))]
+            t = base[: int(rng.integers(0, len(base) + 1))] if rng.integers(0, 2) else base
+            assert M.mp_delete_hashed(p.g, t, p.hashes(t)) == p.o.delete(t)
         p.check_stats()
     # drain: everything released and evicted leaves an empty pool on both sides
     assert M.mp_free(p.g, held) == p.o.free(held) == 0

@@ -170,6 +170,31 @@ def test_insert_refreshes_the_existing_prefix():
     assert p.match(Bq)[1].size == 0 and p.match(A)[1].size == 2
 
 
+def test_delete_script():
+    p = pool(16)
+    A = np.arange(0, 3 * BS, dtype=np.uint32)                                     # a0 a1 a2
+    Bq = np.concatenate([A[:BS], np.arange(100, 100 + 2 * BS, dtype=np.uint32)])  # a0 b1 b2
+    _, a = p.alloc(3)
+    p.insert(A, a)
+    _, b = p.alloc(3)
+    p.insert(Bq, b)                     # adopts b[1], b[2]
+    assert p.delete(A) == (0, 0)        # still referenced: nothing goes
+    p.free(a)
+    p.free(b)
+    free0 = p.stats()["n_free"]
+    assert p.delete(A) == (0, 2)        # a2, a1 go; a0 is shared with Bq and stays
+    assert p.stats()["n_free"] == free0 + 2
+    assert p.alloc(2)[1].tolist() == [int(a[1]), int(a[2])]      # freed deepest first -> a1 on top
+    assert p.match(A)[1].tolist() == [int(a[0])] and p.match(Bq)[1].size == 3
+    assert p.delete(np.arange(900, 900 + BS, dtype=np.uint32)) == (0, 0)   # unknown prompt
+    assert p.delete(Bq[: 2 * BS]) == (0, 0)   # its deepest matched node b1 has a child
+    rc, pin = p.match(Bq[: 2 * BS], flags=O.MATCH_PIN)
+    assert p.delete(Bq) == (0, 1)       # b2 goes, b1 is pinned
+    p.free(pin)
+    assert p.delete(Bq) == (0, 2)       # b1 and, no longer shared, a0
+    assert p.stats()["n_indexed"] == 0
+
+
 def test_evict_on_demand_is_all_or_nothing():
     p = pool(6)
     t = np.arange(4 * BS, dtype=np.uint32)
