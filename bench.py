@@ -82,6 +82,24 @@ def run_step_by_layer(M, src, dst, turn, perm, state, flags, n_layers, bs):
     return total
 
 
+def run_step_per_request(M, src, dst, turn, perm, state, flags):
+    """The unbatched flavour of a step: one mp_match and one mp_transfer_with_insert per request."""
+    total = 0
+    held = []
+    for r in range(len(turn["nblk"])):
+        t = turn["toks"][turn["tok_off"][r]:turn["tok_off"][r + 1]]
+        nblk = int(turn["nblk"][r])
+        rc, m = M.mp_match(dst.h, t, nblk, M.MP_MATCH_PIN)
+        assert rc == 0, M.mp_last_error(dst.h)
+        n = nblk - len(m)
+        rc, d = M.mp_transfer_with_insert(src.h, dst.h, t, len(m), perm[total:total + n], flags=flags)
+        assert rc == 0, M.mp_last_error(src.h)
+        total += n
+        held += [m, d]
+    state["held"].append(np.concatenate(held))
+    return total
+
+
 def run_step(M, src, dst, turn, perm, state, flags):
     """One step.  Returns the number of blocks moved."""
     rc, mb, m = M.mp_match_batch(dst.h, turn["toks"], turn["tok_off"], turn["cap_off"],
@@ -275,6 +293,8 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--direct", action="store_true", help="fused pool-to-pool kernel (no staging)")
     ap.add_argument("--sync", action="store_true", help="every call waits for its device work")
+    ap.add_argument("--per-request", action="store_true",
+                    help="one mp_match + mp_transfer_with_insert per request instead of batched calls")
     ap.add_argument("--by-layer", action="store_true",
                     help="ship one layer per call (mp_transfer_layers) instead of whole blocks")
     ap.add_argument("--host-tier", action="store_true", help="config 5 HBM <-> pinned-host variant")
@@ -350,7 +370,9 @@ def main():
 
     def do_step(i):
         ep, t = divmod(i, n_turns)
-        if args.by_layer:
+        if args.per_request:
+            moved = run_step_per_request(M, src, dst, epochs[ep][t], perms[i], state, flags)
+        elif args.by_layer:
             moved = run_step_by_layer(M, src, dst, epochs[ep][t], perms[i], state,
                                       flags & ~M.MP_EVICT_ON_DEMAND, L, bs)
         else:
@@ -436,6 +458,7 @@ def main():
             "path": "direct (fused pool->pool)" if args.direct else "staged (gather -> staging -> scatter)",
             "granularity": "by-layer (one mp_transfer_layers call per layer)" if args.by_layer
                            else "by-request (whole blocks)",
+            "batching": "one call per request" if args.per_request else "one batched call per step",
             "calls": "synchronous" if args.sync else "MP_ASYNC (host work of the next step overlaps the copy kernels)",
             "blocks_moved": moved,
             "payload_GiB": round(payload / 2**30, 3),

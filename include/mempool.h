@@ -224,7 +224,8 @@ int mp_profile_read(mp_pool_t *p, int kind, double *total_ms_out, uint64_t *laun
  * key: "order" (0 record-major, 1 plane-major), "unroll" (1,2,4,8), "wg_per_cu" (0 = one
  * workgroup per tile group, >0 = persistent grid of that many workgroups per CU),
  * "nontemporal" (0/1), "waves_per_wg" (1 or 4), "xcd_contiguous" (0/1: each XCD walks one
- * contiguous eighth of the work instead of every eighth workgroup). */
+ * contiguous eighth of the work instead of every eighth workgroup), "item_limit" (>0: cap on
+ * wave-items per launch, so a table is cut into several launches; 0 = 2^31-1). */
 int mp_set_tunable(mp_pool_t *p, const char *key, int value);
 
 /* Calibration yardstick: one contiguous device-to-device copy of `bytes` (multiple of 16;

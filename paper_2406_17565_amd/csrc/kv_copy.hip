@@ -13,6 +13,8 @@
 // (entry, plane, chunk) split uses multiply-shift division by launch invariants.
 #include "kv_copy.hpp"
 
+#include <algorithm>
+
 namespace mempool {
 
 FastDiv make_fastdiv(uint32_t d) {
@@ -156,8 +158,9 @@ hipError_t launch_block_copy(const CopySide &src, const CopySide &dst, uint32_t 
   const uint64_t per_entry = (uint64_t)n_planes * chunks;
 
   // keep every item index below 2^31: split very large tables into several launches
-  const uint32_t max_entries = (uint32_t)(0x7fffffffull / per_entry);
-  if (max_entries == 0) return hipErrorInvalidValue;
+  const uint64_t item_cap = tune.item_limit > 0 ? (uint64_t)tune.item_limit : 0x7fffffffull;
+  const uint32_t max_entries = (uint32_t)std::max<uint64_t>(item_cap / per_entry, 1);
+  if (per_entry > 0x7fffffffull) return hipErrorInvalidValue;
 
   for (uint32_t first = 0; first < n; first += max_entries) {
     const uint32_t cnt = (n - first < max_entries) ? n - first : max_entries;

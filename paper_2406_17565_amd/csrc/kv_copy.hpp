@@ -27,6 +27,8 @@ struct CopyTune {
   int nontemporal = -1;     // stream past the caches
   int waves_per_wg = -1;    // 1 or 4 wavefronts per workgroup
   int xcd_contiguous = -1;  // 1: each XCD walks one contiguous eighth of the work items
+  int item_limit = 0;       // >0: at most this many wave-items per launch (tests of the
+                            // multi-launch split); 0 = the kernel's index range, 2^31-1
 };
 
 // Fills every field of `t` that is still -1.  Measured on MI355X (sweeps over all five

@@ -61,6 +61,10 @@ struct DeviceCtx {
   MirrorBuf tokens;              // concatenated prompts
   MirrorBuf offsets;             // [tok_off][blk_off]
   MirrorBuf hashes;
+  // the pinned buffers above still hold the last hashed batch: a transfer_with_insert that
+  // follows a match of the same prompts reuses the hashes instead of launching again
+  bool hash_cache_valid = false;
+  uint32_t hash_cache_n_req = 0;
   hipEvent_t slot_filled[2] = {nullptr, nullptr};   // main -> side (or side -> main)
   hipEvent_t slot_drained[2] = {nullptr, nullptr};  // the other direction
   bool slot_busy[2] = {false, false};
@@ -208,6 +212,14 @@ int device_hashes(mp_pool *p, const uint32_t *tokens, const uint32_t *tok_off, u
   for (uint32_t r = 0; r < n_req; ++r)
     blk_off_out[r + 1] = blk_off_out[r] + (tok_off[r + 1] - tok_off[r]) / bs;
   const uint32_t total_blk = blk_off_out[n_req];
+  if (d.hash_cache_valid && !on_device && d.hash_cache_n_req == n_req && total_blk &&
+      std::memcmp(d.offsets.host, tok_off, 4ull * (n_req + 1)) == 0 &&
+      std::memcmp(d.tokens.host, tokens, 4ull * total_tok) == 0) {
+    *host_tokens = tokens;
+    *host_hashes = (const uint64_t *)d.hashes.host;
+    return MP_OK;
+  }
+  d.hash_cache_valid = false;
   if ((rc = reserve(p, d.tokens, std::max<size_t>(4, 4ull * total_tok), false)) != MP_OK) return rc;
   if ((rc = reserve(p, d.offsets, 8ull * (n_req + 1), false)) != MP_OK) return rc;
   if ((rc = reserve(p, d.hashes, std::max<size_t>(8, 8ull * total_blk), false)) != MP_OK) return rc;
@@ -236,6 +248,8 @@ int device_hashes(mp_pool *p, const uint32_t *tokens, const uint32_t *tok_off, u
                                  (uint64_t *)d.hashes.host, d.stream));
   }
   HIP_TRY(p, hipStreamSynchronize(d.stream));
+  d.hash_cache_valid = !on_device;
+  d.hash_cache_n_req = n_req;
   return MP_OK;
 }
 
@@ -993,6 +1007,7 @@ int mp_set_tunable(mp_pool_t *p, const char *key, int value) {
   else if (k == "nontemporal" && (dflt || value == 0 || value == 1)) p->tune.nontemporal = value;
   else if (k == "waves_per_wg" && (dflt || value == 1 || value == 4)) p->tune.waves_per_wg = value;
   else if (k == "xcd_contiguous" && (dflt || value == 0 || value == 1)) p->tune.xcd_contiguous = value;
+  else if (k == "item_limit" && value >= 0) p->tune.item_limit = value;
   else return fail(p, MP_EINVAL, "unknown tunable or value out of range");
   return MP_OK;
 }

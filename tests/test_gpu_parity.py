@@ -127,6 +127,31 @@ def test_gather_scatter_all_launch_shapes(gpu, name):
     g.close()
 
 
+def test_tables_split_over_several_launches(gpu):
+    """A table whose wave-item count exceeds the per-launch index range is cut into several
+    launches; forced here with a tiny limit."""
+    M, TorchPool = gpu
+    geom = GEOMS["f20k"]
+    NB, n = 50, 37
+    o, g = make_pair(gpu, geom, NB, 11, staging_blocks=n)
+    rng = np.random.default_rng(12)
+    tbl = W.random_table(rng, NB, n)
+    for limit, order in ((100, 0), (61, 1), (1, 0)):      # 60 items per entry at unroll 1
+        assert M.mp_set_tunable(g.h, "item_limit", limit) == 0
+        assert M.mp_set_tunable(g.h, "order", order) == 0
+        g.staging.zero_()
+        assert M.mp_gather(g.h, tbl) == 0
+        assert np.array_equal(g.staging_bytes(n), o.gather(tbl)), limit
+        o2 = O.OraclePool(*geom, NB, data=o.data.copy())
+        dst_tbl = W.random_table(rng, NB, n)
+        o2.scatter(dst_tbl, o.gather(tbl))
+        before = g.bytes()
+        assert M.mp_scatter(g.h, dst_tbl) == 0
+        assert np.array_equal(g.bytes(), o2.data), limit
+        g.load(before)
+    g.close()
+
+
 def test_special_bit_patterns_survive(gpu):
     M, TorchPool = gpu
     geom = GEOMS["tiny"]
