@@ -293,6 +293,8 @@ def main():
     ap.add_argument("--config", type=int, default=3)
     ap.add_argument("--direct", action="store_true", help="fused pool-to-pool kernel (no staging)")
     ap.add_argument("--sync", action="store_true", help="every call waits for its device work")
+    ap.add_argument("--aggregated", action="store_true",
+                    help="both pools in the aggregated layout (the paper's block aggregation)")
     ap.add_argument("--per-request", action="store_true",
                     help="one mp_match + mp_transfer_with_insert per request instead of batched calls")
     ap.add_argument("--by-layer", action="store_true",
@@ -339,8 +341,9 @@ def main():
         biggest = max(int(t["nblk"].sum()) for t in epoch0) + 64
     staging_blocks = biggest if biggest * geom.B <= (8 << 30) else (4 << 30) // geom.B
     s_src, s_dst = torch.cuda.Stream(), torch.cuda.Stream()
-    src = TorchPool(L, H, D, bs, e, NB_src, staging_blocks=staging_blocks, stream=s_src)
-    dst = TorchPool(L, H, D, bs, e, NB_dst, stream=s_dst)
+    layout = M.MP_LAYOUT_AGGREGATED if args.aggregated else M.MP_LAYOUT_DEFAULT
+    src = TorchPool(L, H, D, bs, e, NB_src, staging_blocks=staging_blocks, stream=s_src, layout=layout)
+    dst = TorchPool(L, H, D, bs, e, NB_dst, stream=s_dst, layout=layout)
     # KV fill: N(0,1) in the model dtype, plane by plane (harness work, not the path)
     torch.manual_seed(args.config)
     tdt = torch.bfloat16 if geom.dtype == "bf16" else torch.float16
@@ -456,6 +459,7 @@ def main():
                         f"pools {NB_src}/{NB_dst} blocks ({geom.pool_bytes(NB_src) / 2**30:.0f}/"
                         f"{geom.pool_bytes(NB_dst) / 2**30:.0f} GiB), staging {staging_blocks} blocks",
             "path": "direct (fused pool->pool)" if args.direct else "staged (gather -> staging -> scatter)",
+            "pool_layout": "aggregated [NB][L][2][F]" if args.aggregated else "discrete [L][2][NB][F]",
             "granularity": "by-layer (one mp_transfer_layers call per layer)" if args.by_layer
                            else "by-request (whole blocks)",
             "batching": "one call per request" if args.per_request else "one batched call per step",

@@ -12,10 +12,12 @@
  *                contiguous.  This is the engine's "block"; bs tokens need 2*L of them.
  *   record     : the 2*L fragments of one run of bs tokens laid end to end, B = 2*L*F bytes.
  *                This is the paper's aggregated block.
- *   HBM pool   (MP_TIER_HBM, "discrete" layout)  : [L][2][NB][F] bytes; fragment (l,kv,b)
- *                starts at byte ((l*2+kv)*NB + b)*F of `base`.
- *   host pool  (MP_TIER_HOST_PINNED, aggregated) : [NB][L][2][F] bytes; block b is the
- *                contiguous record at byte b*B of `base`.
+ *   discrete layout   : [L][2][NB][F] bytes; fragment (l,kv,b) starts at byte
+ *                ((l*2+kv)*NB + b)*F of `base`.  The engine's native layout (two blocks per
+ *                layer); the default for an HBM pool.
+ *   aggregated layout : [NB][L][2][F] bytes; block b is the contiguous record at byte b*B of
+ *                `base` (the paper's block aggregation).  Always used by a pinned-host pool;
+ *                an HBM pool may opt in with MP_LAYOUT_AGGREGATED.
  *   staging    : [n][L][2][F] bytes, record i (the i-th entry of a block table) at i*B.
  *   F must be a multiple of 16 bytes.  The copy never looks inside a fragment.
  *
@@ -61,6 +63,11 @@ typedef struct mp_pool mp_pool_t; /* opaque, library-owned */
 #define MP_TIER_HBM 0u
 #define MP_TIER_HOST_PINNED 1u
 
+/* pool memory layout (paper section 5.2: original discrete blocks vs aggregated blocks) */
+#define MP_LAYOUT_DEFAULT 0u    /* discrete for an HBM pool, aggregated for a host pool */
+#define MP_LAYOUT_DISCRETE 1u   /* HBM pools only */
+#define MP_LAYOUT_AGGREGATED 2u
+
 /* return codes */
 #define MP_OK 0
 #define MP_EINVAL (-1)     /* null pointer, id out of range, id not held, duplicate dst id, ... */
@@ -89,6 +96,8 @@ typedef struct {
   void *staging;         /* caller-owned DEVICE buffer for records; may be NULL */
   uint64_t staging_bytes;
   void *stream;          /* hipStream_t; NULL = the default stream */
+  uint32_t layout;       /* MP_LAYOUT_* */
+  uint32_t reserved;     /* must be 0 */
 } mp_pool_desc_t;
 
 typedef struct {

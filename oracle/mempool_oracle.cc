@@ -41,6 +41,7 @@ struct Node {
 
 struct orc_pool {
   uint32_t L, H, D, bs, e, NB, tier, instance_id;
+  bool aggregated;  // [NB][L][2][F] instead of [L][2][NB][F]
   uint64_t seed;
   uint64_t F, B;
   uint8_t *base;
@@ -248,11 +249,13 @@ void orc_block_hashes(const uint32_t *tokens, uint32_t n_tokens, uint32_t bs, ui
 // ---- pool -------------------------------------------------------------------------------
 orc_pool_t *orc_pool_create(uint32_t L, uint32_t H, uint32_t D, uint32_t bs, uint32_t e,
                             uint32_t NB, uint32_t tier, uint32_t instance_id, uint64_t seed,
-                            uint8_t *base) {
-  if (!L || !H || !D || !bs || !e || !NB || !base || tier > 1) return nullptr;
+                            uint8_t *base, uint32_t layout) {
+  if (!L || !H || !D || !bs || !e || !NB || !base || tier > 1 || layout > 2) return nullptr;
+  if (tier == ORC_TIER_HOST && layout == 1) return nullptr;  // a host pool is always aggregated
   orc_pool *p = new orc_pool;
   p->L = L; p->H = H; p->D = D; p->bs = bs; p->e = e; p->NB = NB;
   p->tier = tier; p->instance_id = instance_id; p->seed = seed; p->base = base;
+  p->aggregated = layout == 2 || (layout == 0 && tier == ORC_TIER_HOST);
   p->F = (uint64_t)bs * H * D * e;
   p->B = 2ull * L * p->F;
   p->ref.assign(NB, 0);
@@ -270,10 +273,11 @@ void orc_pool_destroy(orc_pool_t *p) {
 uint64_t orc_fragment_bytes(const orc_pool_t *p) { return p->F; }
 uint64_t orc_record_bytes(const orc_pool_t *p) { return p->B; }
 
-// Where fragment (l, kv, b) starts.  HBM pool: [L][2][NB][F] (the engine's discrete layout,
-// two blocks per layer); host pool: [NB][L][2][F] (aggregated, one record per block).
+// Where fragment (l, kv, b) starts.  Discrete layout [L][2][NB][F] (the engine's own, two
+// blocks per layer; default for HBM) or aggregated layout [NB][L][2][F] (one record per block,
+// section 5.2; always for a host pool, optional for HBM).
 uint64_t orc_fragment_offset(const orc_pool_t *p, uint32_t l, uint32_t kv, uint32_t b) {
-  if (p->tier == ORC_TIER_HBM) return (((uint64_t)l * 2 + kv) * p->NB + b) * p->F;
+  if (!p->aggregated) return (((uint64_t)l * 2 + kv) * p->NB + b) * p->F;
   return (((uint64_t)b * p->L + l) * 2 + kv) * p->F;
 }
 

@@ -51,7 +51,7 @@ void orc_block_hashes(const uint32_t *tokens, uint32_t n_tokens, uint32_t bs, ui
 /* pool over caller-owned bytes `base` (2*L*NB*F bytes) */
 orc_pool_t *orc_pool_create(uint32_t L, uint32_t H, uint32_t D, uint32_t bs, uint32_t e,
                             uint32_t NB, uint32_t tier, uint32_t instance_id, uint64_t seed,
-                            uint8_t *base);
+                            uint8_t *base, uint32_t layout /* 0 default, 1 discrete, 2 aggregated */);
 void orc_pool_destroy(orc_pool_t *p);
 uint64_t orc_fragment_bytes(const orc_pool_t *p);
 uint64_t orc_record_bytes(const orc_pool_t *p);

@@ -37,7 +37,7 @@ def lib():
         L.orc_block_hashes.restype = None
         L.orc_block_hashes.argtypes = [vp, C.c_uint32, C.c_uint32, C.c_uint64, vp]
         L.orc_pool_create.restype = vp
-        L.orc_pool_create.argtypes = [C.c_uint32] * 8 + [C.c_uint64, vp]
+        L.orc_pool_create.argtypes = [C.c_uint32] * 8 + [C.c_uint64, vp, C.c_uint32]
         L.orc_pool_destroy.restype = None
         L.orc_pool_destroy.argtypes = [vp]
         L.orc_fragment_bytes.restype = C.c_uint64
@@ -106,7 +106,8 @@ def block_hashes(tokens, bs: int, seed: int = 0) -> np.ndarray:
 class OraclePool:
     """A pool over a numpy byte array that the oracle reads and writes in place."""
 
-    def __init__(self, L, H, D, bs, e, NB, tier=TIER_HBM, instance_id=0, seed=0, data=None):
+    def __init__(self, L, H, D, bs, e, NB, tier=TIER_HBM, instance_id=0, seed=0, data=None,
+                 layout=0):
         self.geom = (L, H, D, bs, e)
         self.NB, self.tier, self.bs = NB, tier, bs
         self.F = bs * H * D * e
@@ -116,7 +117,8 @@ class OraclePool:
             data = np.zeros(nbytes, dtype=np.uint8)
         assert data.dtype == np.uint8 and data.size == nbytes and data.flags.c_contiguous
         self.data = data
-        self.h = lib().orc_pool_create(L, H, D, bs, e, NB, tier, instance_id, seed, _ptr(data))
+        self.h = lib().orc_pool_create(L, H, D, bs, e, NB, tier, instance_id, seed, _ptr(data),
+                                       layout)
         if not self.h:
             raise ValueError("orc_pool_create refused the geometry")
 

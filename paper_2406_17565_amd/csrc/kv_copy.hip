@@ -27,8 +27,8 @@ FastDiv make_fastdiv(uint32_t d) {
   return f;
 }
 
-CopyTune default_tune(CopyTune t, uint64_t frag_bytes, bool both_sides_tabled) {
-  if (t.order < 0) t.order = both_sides_tabled ? 1 : 0;
+CopyTune default_tune(CopyTune t, uint64_t frag_bytes, bool both_sides_discrete_pools) {
+  if (t.order < 0) t.order = both_sides_discrete_pools ? 1 : 0;
   if (t.unroll < 0) t.unroll = 1;
   if (t.wg_per_cu < 0) t.wg_per_cu = 0;
   if (t.nontemporal < 0) t.nontemporal = 1;
@@ -146,7 +146,11 @@ hipError_t launch_block_copy(const CopySide &src, const CopySide &dst, uint32_t 
                              uint32_t n_planes, uint64_t frag_bytes, const CopyTune &tune_in,
                              int n_cus, hipStream_t stream) {
   if (n == 0) return hipSuccess;
-  const CopyTune tune = default_tune(tune_in, frag_bytes, src.tbl != nullptr && dst.tbl != nullptr);
+  // plane-major walking pays off only when both ends are discrete-layout pools
+  const bool both_discrete = src.tbl != nullptr && dst.tbl != nullptr &&
+                             src.plane_stride > src.block_stride &&
+                             dst.plane_stride > dst.block_stride;
+  const CopyTune tune = default_tune(tune_in, frag_bytes, both_discrete);
   if (!src.base || !dst.base || n_planes == 0 || frag_bytes == 0 || (frag_bytes & 15u) ||
       (frag_bytes >> 4) > 0x7fffffffull)
     return hipErrorInvalidValue;

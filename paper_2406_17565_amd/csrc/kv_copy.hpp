@@ -34,9 +34,10 @@ struct CopyTune {
 // Fills every field of `t` that is still -1.  Measured on MI355X (sweeps over all five
 // geometries): one 16-byte load per lane and one-wave workgroups give the most bandwidth
 // (many small independent waves beat deep unrolling); walking records is best when one side
-// is contiguous staging, walking planes when both sides are pools (fused copy); the per-XCD
+// is contiguous staging or an aggregated pool, walking planes when both sides are discrete
+// pools (fused copy); the per-XCD
 // contiguous walk helps for fragments of 64 KiB and more.
-CopyTune default_tune(CopyTune t, uint64_t frag_bytes, bool both_sides_tabled);
+CopyTune default_tune(CopyTune t, uint64_t frag_bytes, bool both_sides_discrete_pools);
 
 // Unsigned division by an invariant divisor for numerators below 2^31:
 // x / d == (x * m) >> s.

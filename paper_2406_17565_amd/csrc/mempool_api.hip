@@ -109,6 +109,11 @@ int fail_hip(mp_pool *p, hipError_t e, const char *where) {
     if (e_ != hipSuccess) return fail_hip(pool, e_, #expr);  \
   } while (0)
 
+bool aggregated(const mp_pool *p) {
+  return p->desc.layout == MP_LAYOUT_AGGREGATED ||
+         (p->desc.layout == MP_LAYOUT_DEFAULT && p->desc.tier == MP_TIER_HOST_PINNED);
+}
+
 bool same_geometry(const mp_pool *a, const mp_pool *b) {
   return a->desc.n_layers == b->desc.n_layers && a->desc.n_kv_heads == b->desc.n_kv_heads &&
          a->desc.head_dim == b->desc.head_dim && a->desc.block_size == b->desc.block_size &&
@@ -296,7 +301,7 @@ int upload_tables(mp_pool *x, const int32_t *src_ids, const int32_t *dst_ids, ui
 CopySide pool_side(const mp_pool *p, const int32_t *d_tbl, uint32_t l0 = 0) {
   CopySide s;
   s.tbl = d_tbl;
-  if (p->desc.tier == MP_TIER_HBM) {  // discrete layout [L][2][NB][F]
+  if (!aggregated(p)) {  // discrete layout [L][2][NB][F]
     s.plane_stride = (uint64_t)p->desc.n_blocks * p->F;
     s.block_stride = p->F;
   } else {  // aggregated layout [NB][L][2][F]
@@ -630,6 +635,8 @@ int mp_pool_create(const mp_pool_desc_t *desc, mp_pool_t **out) {
       !desc->elem_bytes || !desc->n_blocks || !desc->base)
     return MP_EINVAL;
   if (desc->tier != MP_TIER_HBM && desc->tier != MP_TIER_HOST_PINNED) return MP_EINVAL;
+  if (desc->layout > MP_LAYOUT_AGGREGATED || desc->reserved != 0) return MP_EINVAL;
+  if (desc->tier == MP_TIER_HOST_PINNED && desc->layout == MP_LAYOUT_DISCRETE) return MP_EINVAL;
   if (desc->n_blocks > 0x7fffffffu || desc->n_layers > 0x7fffu) return MP_EINVAL;
   const uint64_t F = (uint64_t)desc->block_size * desc->n_kv_heads * desc->head_dim * desc->elem_bytes;
   if (F % 16 != 0 || F > (1ull << 34)) return MP_EINVAL;

@@ -13,6 +13,7 @@ import numpy as np
 from . import build as _build
 
 MP_TIER_HBM, MP_TIER_HOST_PINNED = 0, 1
+MP_LAYOUT_DEFAULT, MP_LAYOUT_DISCRETE, MP_LAYOUT_AGGREGATED = 0, 1, 2
 MP_OK, MP_EINVAL, MP_ESHAPE, MP_ENOMEM, MP_ENOSTAGING, MP_EHIP, MP_ESTALE = 0, -1, -2, -3, -4, -5, -6
 MP_DST_GIVEN, MP_EVICT_ON_DEMAND, MP_ASYNC = 0x01, 0x02, 0x04
 MP_MATCH_PIN, MP_TOKENS_ON_DEVICE, MP_DIRECT = 0x08, 0x10, 0x20
@@ -33,7 +34,8 @@ class mp_pool_desc_t(C.Structure):
     _fields_ = [(n, C.c_uint32) for n in ("n_layers", "n_kv_heads", "head_dim", "block_size",
                                           "elem_bytes", "n_blocks", "tier", "instance_id")] + [
         ("hash_seed", C.c_uint64), ("base", C.c_void_p), ("staging", C.c_void_p),
-        ("staging_bytes", C.c_uint64), ("stream", C.c_void_p)]
+        ("staging_bytes", C.c_uint64), ("stream", C.c_void_p), ("layout", C.c_uint32),
+        ("reserved", C.c_uint32)]
 
 
 class mp_pool_stats_t(C.Structure):
@@ -120,9 +122,9 @@ def _ptr(a):
 # ---- same names as the C header ------------------------------------------------------------
 def mp_pool_create(n_layers, n_kv_heads, head_dim, block_size, elem_bytes, n_blocks, base,
                    tier=MP_TIER_HBM, instance_id=0, hash_seed=0, staging=None, staging_bytes=0,
-                   stream=None):
+                   stream=None, layout=MP_LAYOUT_DEFAULT):
     d = mp_pool_desc_t(n_layers, n_kv_heads, head_dim, block_size, elem_bytes, n_blocks, tier,
-                       instance_id, hash_seed, base, staging, staging_bytes, stream)
+                       instance_id, hash_seed, base, staging, staging_bytes, stream, layout, 0)
     h = C.c_void_p()
     rc = lib().mp_pool_create(C.byref(d), C.byref(h))
     return rc, (h.value if rc == MP_OK else None)

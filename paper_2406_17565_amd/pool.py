@@ -11,9 +11,11 @@ from . import mempool as M
 
 class TorchPool:
     def __init__(self, L, H, D, bs, e, NB, tier=M.MP_TIER_HBM, staging_blocks=0, seed=0,
-                 instance_id=0, device="cuda:0", stream=None):
+                 instance_id=0, device="cuda:0", stream=None, layout=M.MP_LAYOUT_DEFAULT):
         self.geom = (L, H, D, bs, e)
         self.NB, self.tier, self.bs = NB, tier, bs
+        self.aggregated = layout == M.MP_LAYOUT_AGGREGATED or (
+            layout == M.MP_LAYOUT_DEFAULT and tier == M.MP_TIER_HOST_PINNED)
         self.F = bs * H * D * e
         self.B = 2 * L * self.F
         nbytes = 2 * L * NB * self.F
@@ -30,7 +32,7 @@ class TorchPool:
             hash_seed=seed,
             staging=self.staging.data_ptr() if self.staging is not None else None,
             staging_bytes=self.staging.numel() if self.staging is not None else 0,
-            stream=self.stream.cuda_stream or None)
+            stream=self.stream.cuda_stream or None, layout=layout)
         if rc != M.MP_OK:
             raise ValueError(f"mp_pool_create: {M.mp_strerror(rc)}")
 

@@ -31,13 +31,13 @@ GEOMS = {  # name: (L, H, D, bs, e)
 }
 
 
-def make_pair(gpu, geom, NB, seed, staging_blocks, tier=0, hash_seed=0):
+def make_pair(gpu, geom, NB, seed, staging_blocks, tier=0, hash_seed=0, layout=0):
     M, TorchPool = gpu
     L, H, D, bs, e = geom
     rng = np.random.default_rng(seed)
     data = W.kv_bytes(rng, 2 * L * NB * bs * H * D * e)
-    o = O.OraclePool(*geom, NB, tier=tier, seed=hash_seed, data=data.copy())
-    g = TorchPool(*geom, NB, tier=tier, staging_blocks=staging_blocks, seed=hash_seed)
+    o = O.OraclePool(*geom, NB, tier=tier, seed=hash_seed, data=data.copy(), layout=layout)
+    g = TorchPool(*geom, NB, tier=tier, staging_blocks=staging_blocks, seed=hash_seed, layout=layout)
     g.load(data)
     return o, g
 
@@ -537,3 +537,32 @@ def test_transfer_layers(gpu, mode):
     _same_state(ho, hg)
     for p in (sg, dg, hg):
         p.close()
+
+
+@pytest.mark.parametrize("layouts", [(2, 2), (2, 0), (0, 2)])
+def test_aggregated_hbm_pools(gpu, layouts):
+    """HBM pools that opted into the aggregated layout, on either or both ends."""
+    M, TorchPool = gpu
+    geom = GEOMS["f480"]
+    so, sg = make_pair(gpu, geom, 40, 4, staging_blocks=5, layout=layouts[0])
+    do, dg = make_pair(gpu, geom, 30, 5, staging_blocks=0, layout=layouts[1])
+    M.mp_alloc(sg.h, 40)
+    so.alloc(40)
+    rng = np.random.default_rng(8)
+    for flags in (0, M.MP_DIRECT):
+        tbl = rng.integers(0, 40, 11).astype(np.int32)
+        rc, d = M.mp_transfer(sg.h, dg.h, tbl, flags=flags)
+        rco, d_o = O.transfer(so, do, tbl)
+        assert rc == rco == 0 and d.tolist() == d_o.tolist(), M.mp_last_error(sg.h)
+        _same_state(do, dg)
+    assert M.mp_gather(sg.h, tbl[:5]) == 0
+    assert np.array_equal(sg.staging_bytes(5), so.gather(tbl[:5]))
+    rc, ids = M.mp_alloc(dg.h, 3)
+    do.alloc(3)
+    assert M.mp_transfer_layers(sg.h, dg.h, tbl[:3], ids, 0, 1, 0) == 0
+    assert O.transfer_layers(so, do, tbl[:3], ids, 0, 1) == 0
+    _same_state(do, dg)
+    sg.close()
+    dg.close()
+    assert M.mp_pool_create(*geom, 8, 4096, tier=M.MP_TIER_HOST_PINNED,
+                            layout=M.MP_LAYOUT_DISCRETE)[0] == M.MP_EINVAL

@@ -36,6 +36,10 @@ def test_sizes_follow_the_paper(geom):
     assert h.fragment_offset(0, 0, 3) == 3 * p.B   # aggregated layout: block = one record
     assert h.fragment_offset(0, 1, 0) == p.F
     assert h.fragment_offset(1, 0, 0) == 2 * p.F
+    a = O.OraclePool(L, H, D, bs, e, 8, layout=2)   # an HBM pool that opted into aggregation
+    assert [a.fragment_offset(*x) for x in ((0, 0, 3), (0, 1, 0), (1, 0, 0))] == [3 * p.B, p.F, 2 * p.F]
+    with pytest.raises(ValueError):
+        O.OraclePool(L, H, D, bs, e, 8, tier=O.TIER_HOST, layout=1)
 
 
 @pytest.mark.parametrize("geom", GEOMS)
@@ -178,3 +182,15 @@ def test_transfer_layers_is_a_slice_of_the_transfer():
     assert O.transfer_layers(src, a, s_ids, [3, 3, 5, 1], 0, 1) == O.EINVAL
     assert O.transfer_layers(src, a, s_ids, [3, 0, 5, 7], 0, 1) == O.EINVAL   # 7 not held
     assert np.array_equal(a.data, b.data)
+
+
+def test_aggregated_hbm_pool_is_the_staging_layout():
+    geom = GEOMS[0]
+    src = _pool(geom, 10, 30)
+    src.alloc(10)
+    agg = O.OraclePool(*geom, 6, layout=2)
+    rc, d = O.transfer(src, agg, [7, 1, 4], None)
+    assert rc == 0
+    # block d[i] of an aggregated pool IS record i of the gather
+    assert np.array_equal(agg.data.reshape(6, src.B)[d], src.gather([7, 1, 4]).reshape(3, src.B))
+    assert np.array_equal(agg.gather(d), src.gather([7, 1, 4]))
