@@ -27,13 +27,16 @@ FastDiv make_fastdiv(uint32_t d) {
   return f;
 }
 
-CopyTune default_tune(CopyTune t, uint64_t frag_bytes, bool both_sides_discrete_pools) {
+CopyTune default_tune(CopyTune t, uint64_t frag_bytes, bool both_sides_discrete_pools,
+                      bool dst_is_discrete_pool) {
   if (t.order < 0) t.order = both_sides_discrete_pools ? 1 : 0;
   if (t.unroll < 0) t.unroll = 1;
   if (t.wg_per_cu < 0) t.wg_per_cu = 0;
   if (t.nontemporal < 0) t.nontemporal = 1;
   if (t.waves_per_wg < 0) t.waves_per_wg = 1;
-  if (t.xcd_contiguous < 0) t.xcd_contiguous = frag_bytes >= (64u << 10) ? 1 : 0;
+  if (t.xcd_contiguous < 0)
+    t.xcd_contiguous =
+        (frag_bytes >= (64u << 10) || (frag_bytes >= (16u << 10) && dst_is_discrete_pool)) ? 1 : 0;
   return t;
 }
 
@@ -150,7 +153,8 @@ hipError_t launch_block_copy(const CopySide &src, const CopySide &dst, uint32_t 
   const bool both_discrete = src.tbl != nullptr && dst.tbl != nullptr &&
                              src.plane_stride > src.block_stride &&
                              dst.plane_stride > dst.block_stride;
-  const CopyTune tune = default_tune(tune_in, frag_bytes, both_discrete);
+  const bool dst_discrete = dst.tbl != nullptr && dst.plane_stride > dst.block_stride;
+  const CopyTune tune = default_tune(tune_in, frag_bytes, both_discrete, dst_discrete);
   if (!src.base || !dst.base || n_planes == 0 || frag_bytes == 0 || (frag_bytes & 15u) ||
       (frag_bytes >> 4) > 0x7fffffffull)
     return hipErrorInvalidValue;

@@ -36,8 +36,10 @@ struct CopyTune {
 // (many small independent waves beat deep unrolling); walking records is best when one side
 // is contiguous staging or an aggregated pool, walking planes when both sides are discrete
 // pools (fused copy); the per-XCD
-// contiguous walk helps for fragments of 64 KiB and more.
-CopyTune default_tune(CopyTune t, uint64_t frag_bytes, bool both_sides_discrete_pools);
+// contiguous walk helps for fragments of 64 KiB and more, and from 16 KiB when the destination
+// is a discrete pool (scattered writes).
+CopyTune default_tune(CopyTune t, uint64_t frag_bytes, bool both_sides_discrete_pools,
+                      bool dst_is_discrete_pool);
 
 // Unsigned division by an invariant divisor for numerators below 2^31:
 // x / d == (x * m) >> s.
