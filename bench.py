@@ -118,7 +118,7 @@ def run_step(M, src, dst, turn, perm, state, flags):
     return total
 
 
-def cpu_baseline(W, geom, n_sessions=64, n_turns=4, NB_src=2048, NB_dst=8704):
+def cpu_baseline(W, geom, n_sessions=64, n_turns=4, NB_src=4096, NB_dst=8704):
     """The CPU oracle on a bounded sample of the same workload: the four turns of the first set
     of sessions, same geometry, pools cut to what that set needs; single thread."""
     from oracle import oracle as O
