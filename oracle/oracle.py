@@ -123,9 +123,12 @@ class OraclePool:
             raise ValueError("orc_pool_create refused the geometry")
 
     def __del__(self):
-        if getattr(self, "h", None):
-            lib().orc_pool_destroy(self.h)
-            self.h = None
+        try:
+            if getattr(self, "h", None):
+                lib().orc_pool_destroy(self.h)
+                self.h = None
+        except Exception:      # interpreter shutdown: the module globals may be gone already
+            pass
 
     def fragment_offset(self, l, kv, b):
         return lib().orc_fragment_offset(self.h, l, kv, b)

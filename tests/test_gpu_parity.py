@@ -566,3 +566,80 @@ def test_aggregated_hbm_pools(gpu, layouts):
     dg.close()
     assert M.mp_pool_create(*geom, 8, 4096, tier=M.MP_TIER_HOST_PINNED,
                             layout=M.MP_LAYOUT_DISCRETE)[0] == M.MP_EINVAL
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_mixed_features_random(gpu, seed):
+    """Everything interleaved: HBM and host-tier destinations, discrete and aggregated pools,
+    staged / fused / asynchronous transfers, swap-in, by-layer rewrites, delete, evict."""
+    M, TorchPool = gpu
+    geoms = [(3, 1, 8, 4, 2), (2, 2, 64, 16, 2), (1, 5, 24, 2, 2), (4, 3, 40, 8, 2)]
+    rng = np.random.default_rng(1000 + seed)
+    geom = geoms[seed % len(geoms)]
+    bs = geom[3]
+    lay_s, lay_d = int(rng.integers(0, 2)) * 2, int(rng.integers(0, 2)) * 2
+    so, sg = make_pair(gpu, geom, 64, seed, staging_blocks=int(rng.integers(1, 9)), layout=lay_s)
+    do, dg = make_pair(gpu, geom, int(rng.integers(16, 40)), seed + 50,
+                       staging_blocks=int(rng.integers(1, 5)), hash_seed=seed, layout=lay_d)
+    ho, hg = make_pair(gpu, geom, 24, seed + 70, staging_blocks=0, tier=1, hash_seed=seed)
+    M.mp_alloc(sg.h, 64)
+    so.alloc(64)
+    prompts, live, hlive = [], [], []
+    for step in range(60):
+        if prompts and rng.integers(0, 2):
+            base = prompts[int(rng.integers(0, len(prompts)))]
+            t = np.concatenate([base, rng.integers(0, 50, int(rng.integers(1, 3 * bs)), dtype=np.uint32)])
+        else:
+            t = rng.integers(0, 50, int(rng.integers(0, 6 * bs)), dtype=np.uint32)
+        nblk = (len(t) + bs - 1) // bs
+        t_o, t_g, lv = (do, dg, live) if rng.integers(0, 4) else (ho, hg, hlive)
+        rc, m = M.mp_match(t_g.h, t, nblk, M.MP_MATCH_PIN)
+        rco, mo = t_o.match(t, flags=O.MATCH_PIN)
+        assert rc == rco == 0 and m.tolist() == mo.tolist()
+        tbl = rng.integers(0, 64, nblk - len(m)).astype(np.int32)
+        fl = M.MP_EVICT_ON_DEMAND if rng.integers(0, 3) else 0
+        fl |= M.MP_DIRECT if rng.integers(0, 3) == 0 else 0
+        fl |= M.MP_ASYNC if rng.integers(0, 2) else 0
+        rc, d = M.mp_transfer_with_insert(sg.h, t_g.h, t, len(m), tbl, flags=fl)
+        rco, d_o = O.transfer_with_insert(so, t_o, t, len(mo), tbl, flags=fl & 0x3)
+        assert rc == rco, (seed, step, rc, rco, M.mp_last_error(sg.h))
+        torch.cuda.synchronize()
+        if rc == 0:
+            assert d.tolist() == d_o.tolist()
+            prompts.append(t)
+            lv.append(np.concatenate([m, d]))
+        else:
+            lv.append(m)
+        if len(lv) > 3 or rc != 0:
+            ids = lv.pop(int(rng.integers(0, len(lv))))
+            assert M.mp_free(t_g.h, ids) == t_o.free(ids) == 0
+        r = rng.integers(0, 8)
+        if r == 0:
+            k = int(rng.integers(0, 4))
+            assert M.mp_evict(t_g.h, k) == t_o.evict(k)
+        elif r == 1 and prompts:
+            q = prompts[int(rng.integers(0, len(prompts)))]
+            assert M.mp_delete(t_g.h, q) == t_o.delete(q)
+        elif r == 2 and hlive:                      # swap a held host block set into the HBM pool
+            ids = hlive[int(rng.integers(0, len(hlive)))]
+            if len(ids):
+                f2 = M.MP_EVICT_ON_DEMAND | (M.MP_DIRECT if rng.integers(0, 2) else 0)
+                rc, d2 = M.mp_transfer(hg.h, dg.h, ids, flags=f2)
+                rco, d2o = O.transfer(ho, do, ids, flags=O.EVICT_ON_DEMAND)
+                assert rc == rco, (seed, step, rc, rco, M.mp_last_error(hg.h))
+                if rc == 0:
+                    assert d2.tolist() == d2o.tolist()
+                    live.append(d2)
+        elif r == 3 and live:                       # by-layer rewrite of a held destination set
+            ids = np.unique(live[int(rng.integers(0, len(live)))])
+            if len(ids):
+                srcs = rng.integers(0, 64, len(ids)).astype(np.int32)
+                l0 = int(rng.integers(0, geom[0]))
+                l1 = int(rng.integers(l0 + 1, geom[0] + 1))
+                f2 = M.MP_DIRECT if rng.integers(0, 2) else 0
+                assert M.mp_transfer_layers(sg.h, dg.h, srcs, ids, l0, l1, f2) == 0
+                assert O.transfer_layers(so, do, srcs, ids, l0, l1) == 0
+        _same_state(do, dg)
+        _same_state(ho, hg)
+    for p in (sg, dg, hg):
+        p.close()
