@@ -46,7 +46,11 @@
  *   One thread at a time per pool.  Device work of a transfer is enqueued on the SOURCE pool's
  *   stream (the sender executes the transmission, paper section 4.3); hashing for
  *   match/insert runs on the stream of the pool whose index is consulted.  Without MP_ASYNC a
- *   call returns after its device work has completed.
+ *   call returns after its device work has completed.  With MP_ASYNC a transfer returns once
+ *   its work is enqueued: destination ids and the index are already final, the bytes are valid
+ *   in the order of the executing stream (the source pool's; the HBM pool's when the source is
+ *   a host pool).  Until that work has run the caller must not free, evict or overwrite the
+ *   blocks involved, and work on other streams that reads the destination must wait for it.
  */
 #ifndef MEMPOOL_H
 #define MEMPOOL_H

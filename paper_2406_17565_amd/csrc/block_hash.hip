@@ -9,8 +9,8 @@
 // Mapping to the machine: integer work bound by dependent 64-bit multiplies, not by memory
 // (64 B of tokens per block).  One workgroup per prompt.  Stage 1 is parallel: one lane per
 // block computes d_i into LDS.  Stage 2 is the serial chain, two multiplies per block; it is
-// wave-uniform, so it is written on values fetched with readlane and runs on the scalar ALU.
-// Stage 3 writes the tile of hashes back coalesced.
+// wave-uniform, so it is written on values fetched with readlane and runs on the scalar ALU;
+// each h_i is parked in lane i of a result register and stored 64 at a time.
 #include "kv_copy.hpp"
 
 namespace mempool {
@@ -33,6 +33,48 @@ __device__ inline uint64_t fmix64(uint64_t x) {
   return x;
 }
 
+// FNV-1a-64 over the four bytes of one token, least significant byte first.
+__device__ inline uint64_t fnv_token(uint64_t a, uint32_t w) {
+  a = (a ^ (w & 0xffu)) * kFnvPrime;
+  a = (a ^ ((w >> 8) & 0xffu)) * kFnvPrime;
+  a = (a ^ ((w >> 16) & 0xffu)) * kFnvPrime;
+  a = (a ^ (w >> 24)) * kFnvPrime;
+  return a;
+}
+
+// One chain step for block K of the current group of 64: digest from lane K, result to lane K.
+template <int K>
+__device__ inline void chain_step(uint64_t &h, uint32_t dlo, uint32_t dhi, uint32_t &rlo,
+                                  uint32_t &rhi) {
+  const uint64_t d = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(dhi, K) << 32) |
+                     (uint32_t)__builtin_amdgcn_readlane(dlo, K);
+  h = fmix64((h + kGolden) ^ d);
+  const uint32_t lo = (uint32_t)h, hi = (uint32_t)(h >> 32);
+  asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(rlo) : "s"(lo), "n"(K));
+  asm volatile("v_writelane_b32 %0, %1, %2" : "+v"(rhi) : "s"(hi), "n"(K));
+}
+
+template <int K0>
+__device__ inline void chain16(uint64_t &h, uint32_t dlo, uint32_t dhi, uint32_t &rlo,
+                               uint32_t &rhi) {
+  chain_step<K0 + 0>(h, dlo, dhi, rlo, rhi);
+  chain_step<K0 + 1>(h, dlo, dhi, rlo, rhi);
+  chain_step<K0 + 2>(h, dlo, dhi, rlo, rhi);
+  chain_step<K0 + 3>(h, dlo, dhi, rlo, rhi);
+  chain_step<K0 + 4>(h, dlo, dhi, rlo, rhi);
+  chain_step<K0 + 5>(h, dlo, dhi, rlo, rhi);
+  chain_step<K0 + 6>(h, dlo, dhi, rlo, rhi);
+  chain_step<K0 + 7>(h, dlo, dhi, rlo, rhi);
+  chain_step<K0 + 8>(h, dlo, dhi, rlo, rhi);
+  chain_step<K0 + 9>(h, dlo, dhi, rlo, rhi);
+  chain_step<K0 + 10>(h, dlo, dhi, rlo, rhi);
+  chain_step<K0 + 11>(h, dlo, dhi, rlo, rhi);
+  chain_step<K0 + 12>(h, dlo, dhi, rlo, rhi);
+  chain_step<K0 + 13>(h, dlo, dhi, rlo, rhi);
+  chain_step<K0 + 14>(h, dlo, dhi, rlo, rhi);
+  chain_step<K0 + 15>(h, dlo, dhi, rlo, rhi);
+}
+
 __global__ __launch_bounds__(kThreads) void block_hash_kernel(
     const uint32_t *__restrict__ tokens, const uint32_t *__restrict__ tok_off,
     const uint32_t *__restrict__ blk_off, uint32_t bs, uint64_t seed,
@@ -45,22 +87,36 @@ __global__ __launch_bounds__(kThreads) void block_hash_kernel(
   uint64_t h = seed;  // carried by wave 0 across tiles
   for (uint32_t base = 0; base < nblk; base += kTile) {
     const uint32_t cnt = min((uint32_t)kTile, nblk - base);
-    // stage 1: digests
+    // stage 1: digests.  The tokens of a block are fetched in groups of 16 / 4 independent
+    // loads before they are consumed, so a block costs one or two memory round trips (the
+    // tokens may sit in pinned host memory) instead of one per token.
     for (uint32_t j = threadIdx.x; j < cnt; j += kThreads) {
       const uint32_t *t = tokens + t0 + (uint64_t)(base + j) * bs;
       uint64_t a = kFnvOffset;
-      for (uint32_t k = 0; k < bs; ++k) {
-        const uint32_t w = t[k];
-        a = (a ^ (w & 0xffu)) * kFnvPrime;
-        a = (a ^ ((w >> 8) & 0xffu)) * kFnvPrime;
-        a = (a ^ ((w >> 16) & 0xffu)) * kFnvPrime;
-        a = (a ^ (w >> 24)) * kFnvPrime;
+      uint32_t k = 0;
+      for (; k + 16 <= bs; k += 16) {
+        uint32_t w[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) w[i] = t[k + i];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) a = fnv_token(a, w[i]);
       }
+      for (; k + 4 <= bs; k += 4) {
+        uint32_t w[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w[i] = t[k + i];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a = fnv_token(a, w[i]);
+      }
+      for (; k < bs; ++k) a = fnv_token(a, t[k]);
       tile[j] = a;
     }
     __syncthreads();
     // stage 2: chain, on wave 0.  Each lane fetches one digest; step k reads lane k's digest
     // into scalar registers, so h lives in SGPRs and the multiplies issue on the scalar ALU.
+    // A lone wave issues one instruction every four cycles, so the step is kept as short as
+    // possible: no per-step bounds check (16 steps per check), and h_k is parked in lane k of a
+    // result register with v_writelane, to be stored 64 at a time.
     if (threadIdx.x < 64) {
       const uint32_t lane = threadIdx.x;
       // (the lane builtins return int: go through uint32_t so nothing gets sign-extended)
@@ -69,21 +125,17 @@ __global__ __launch_bounds__(kThreads) void block_hash_kernel(
       for (uint32_t jj = 0; jj < cnt; jj += 64) {
         const uint64_t dv = (jj + lane < cnt) ? tile[jj + lane] : 0;
         const uint32_t dlo = (uint32_t)dv, dhi = (uint32_t)(dv >> 32);
-#pragma unroll
-        for (int k = 0; k < 64; ++k) {
-          if (jj + k < cnt) {  // wave-uniform
-            const uint64_t d = ((uint64_t)(uint32_t)__builtin_amdgcn_readlane(dhi, k) << 32) |
-                               (uint32_t)__builtin_amdgcn_readlane(dlo, k);
-            h = fmix64((h + kGolden) ^ d);
-            if (lane == 0) tile[jj + k] = h;  // the digest of step k is already in registers
-          }
-        }
+        uint32_t rlo = 0, rhi = 0;
+        // steps past cnt (at most 15, only in a prompt's last group) chain zeros into a copy
+        // of h that is never used again
+        chain16<0>(h, dlo, dhi, rlo, rhi);
+        if (jj + 16 < cnt) chain16<16>(h, dlo, dhi, rlo, rhi);
+        if (jj + 32 < cnt) chain16<32>(h, dlo, dhi, rlo, rhi);
+        if (jj + 48 < cnt) chain16<48>(h, dlo, dhi, rlo, rhi);
+        if (jj + lane < cnt) out[o0 + base + jj + lane] = ((uint64_t)rhi << 32) | rlo;
       }
     }
-    __syncthreads();
-    // stage 3: write back
-    for (uint32_t j = threadIdx.x; j < cnt; j += kThreads) out[o0 + base + j] = tile[j];
-    __syncthreads();
+    __syncthreads();  // the tile is overwritten by the next round of digests
   }
 }
 
