@@ -28,6 +28,7 @@ GEOMS = {  # name: (L, H, D, bs, e)
     "f32k": (4, 8, 128, 16, 2),         # F = 32 KiB (config 3's fragment), several chunks
     "f2560": (2, 5, 128, 2, 1),         # F = 1280 B with 1-byte elements
     "f20k": (3, 5, 128, 16, 1),         # F = 10 KiB: 2.5 wave-items at unroll 4
+    "f16": (1, 1, 16, 1, 1),            # F = 16 B: one 16-byte vector per fragment, bs = 1
 }
 
 
@@ -43,7 +44,7 @@ def make_pair(gpu, geom, NB, seed, staging_blocks, tier=0, hash_seed=0, layout=0
 
 
 # ---- a1: chained block hash ------------------------------------------------------------------
-@pytest.mark.parametrize("bs", [16, 32, 4])
+@pytest.mark.parametrize("bs", [16, 32, 4, 1, 3, 40])
 def test_block_hashes(gpu, bs):
     M, TorchPool = gpu
     geom = (1, 1, 8, bs, 2)
