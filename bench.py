@@ -531,6 +531,7 @@ def main():
             "traffic": traffic,
             "traffic_source": traffic_src,
             "plain_copy_ceiling_GBs": round(copy_ceiling, 1),
+            "plain_copy_bytes_each_way": cal_bytes,
             "frac_of_plain_copy": round(achieved / copy_ceiling, 4),
             "kernel": "kv_block_copy",
             "launches": k_n,
