@@ -8,7 +8,7 @@ scatter, insert).  Four consecutive steps are the four turns of one set of sessi
 fourth turn the sessions end (their blocks become historical) and a new set starts, so the
 destination pool evicts on demand in steady state.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line.
 """
 import argparse
 import json
