@@ -238,7 +238,10 @@ int mp_profile_read(mp_pool_t *p, int kind, double *total_ms_out, uint64_t *laun
  * workgroup per tile group, >0 = persistent grid of that many workgroups per CU),
  * "nontemporal" (0/1), "waves_per_wg" (1 or 4), "xcd_contiguous" (0/1: each XCD walks one
  * contiguous eighth of the work instead of every eighth workgroup), "item_limit" (>0: cap on
- * wave-items per launch, so a table is cut into several launches; 0 = 2^31-1). */
+ * wave-items per launch, so a table is cut into several launches; 0 = 2^31-1),
+ * "device_probe" (1: keep a copy of the index -- hash table, parent links, node tokens -- in
+ * HBM and let mp_match / mp_match_batch walk it in a kernel right behind the hash kernel; the
+ * host then only stamps, pins and copies out the result.  Same answers as the host walk.) */
 int mp_set_tunable(mp_pool_t *p, const char *key, int value);
 
 /* Calibration yardstick: one contiguous device-to-device copy of `bytes` (multiple of 16;

@@ -6,7 +6,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libmempool.so")
-SOURCES = ["kv_copy.hip", "block_hash.hip", "mempool_api.hip"]
+SOURCES = ["kv_copy.hip", "block_hash.hip", "index_probe.hip", "mempool_api.hip"]
 HEADERS = ["kv_copy.hpp", "pool_index.hpp", os.path.join("..", "..", "include", "mempool.h")]
 
 

@@ -69,4 +69,21 @@ hipError_t launch_block_hash(const uint32_t *tokens, const uint32_t *tok_off,
                              const uint32_t *blk_off, uint32_t n_req, uint32_t bs, uint64_t seed,
                              uint64_t *out, hipStream_t stream);
 
+// Probe of the device-resident index copy for a batch of prompts, right behind the hash kernel.
+//   hashes / hash_off : the chained hashes and their n_req+1 offsets (floor(len/bs) per prompt)
+//   out_off           : n_req+1 slot offsets into ids_out (request r may use out_off[r+1]-out_off[r])
+//   keys/vals/parent/node_tokens : the device copy (capacity a power of two)
+//   ids_out[out_off[r] + i] = block of prompt r's block i for i < n_matched_out[r]
+hipError_t launch_index_probe(const uint32_t *tokens, const uint32_t *tok_off,
+                              const uint32_t *hash_off, const uint64_t *hashes,
+                              const uint32_t *out_off, uint32_t n_req, uint32_t bs,
+                              const uint64_t *keys, const int32_t *vals, const int32_t *parent,
+                              const uint32_t *node_tokens, uint64_t capacity, int32_t *ids_out,
+                              uint32_t *n_matched_out, hipStream_t stream);
+
+// Replays the host index's change log onto the device copy.
+hipError_t launch_index_apply(const uint32_t *slot_upd, uint32_t n_slots, const uint32_t *node_upd,
+                              uint32_t n_nodes, uint32_t bs, uint64_t *keys, int32_t *vals,
+                              int32_t *parent, uint32_t *node_tokens, hipStream_t stream);
+
 }  // namespace mempool

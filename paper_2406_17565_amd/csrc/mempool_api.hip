@@ -65,6 +65,16 @@ struct DeviceCtx {
   // follows a match of the same prompts reuses the hashes instead of launching again
   bool hash_cache_valid = false;
   uint32_t hash_cache_n_req = 0;
+  // device-resident copy of the index (open-addressing table + per-node parent and tokens),
+  // present once the "device_probe" tunable has been switched on
+  bool mirror_on = false;
+  uint64_t mirror_cap = 0;
+  uint64_t *m_keys = nullptr;
+  int32_t *m_vals = nullptr;
+  int32_t *m_parent = nullptr;
+  uint32_t *m_tokens = nullptr;
+  MirrorBuf m_updates;  // pinned change records the apply kernel reads
+  MirrorBuf m_out;      // pinned: [out offsets][matched counts][block ids]
   hipEvent_t slot_filled[2] = {nullptr, nullptr};   // main -> side (or side -> main)
   hipEvent_t slot_drained[2] = {nullptr, nullptr};  // the other direction
   bool slot_busy[2] = {false, false};
@@ -205,9 +215,15 @@ void prof_drain(mp_pool *p) {
 // the n_req+1 offsets into that array.  Host tokens are copied into pinned memory; device
 // tokens are also copied back, because index nodes keep (and compare) their tokens.
 // On return *host_tokens points at a host copy of all tokens.
+int mirror_sync(mp_pool *p);
+int launch_probe(mp_pool *p, const uint32_t *k_tok, uint32_t n_req, const uint32_t *probe_off);
+
+// With probe_off (n_req+1 output slot offsets) the index probe kernel runs right behind the
+// hash kernel, before the one synchronisation; its results land in p->dev.m_out.
 int device_hashes(mp_pool *p, const uint32_t *tokens, const uint32_t *tok_off, uint32_t n_req,
                   bool on_device, std::vector<uint32_t> &blk_off_out,
-                  const uint32_t **host_tokens, const uint64_t **host_hashes) {
+                  const uint32_t **host_tokens, const uint64_t **host_hashes,
+                  const uint32_t *probe_off = nullptr) {
   int rc = ensure_device(p);
   if (rc != MP_OK) return rc;
   DeviceCtx &d = p->dev;
@@ -222,6 +238,10 @@ int device_hashes(mp_pool *p, const uint32_t *tokens, const uint32_t *tok_off, u
       std::memcmp(d.tokens.host, tokens, 4ull * total_tok) == 0) {
     *host_tokens = tokens;
     *host_hashes = (const uint64_t *)d.hashes.host;
+    if (probe_off) {  // the hashes are remembered, the index may have changed: probe again
+      if ((rc = launch_probe(p, (const uint32_t *)d.tokens.host, n_req, probe_off)) != MP_OK) return rc;
+      HIP_TRY(p, hipStreamSynchronize(d.stream));
+    }
     return MP_OK;
   }
   d.hash_cache_valid = false;
@@ -252,9 +272,102 @@ int device_hashes(mp_pool *p, const uint32_t *tokens, const uint32_t *tok_off, u
     HIP_TRY(p, launch_block_hash(k_tok, h_off, h_off + n_req + 1, n_req, bs, p->desc.hash_seed,
                                  (uint64_t *)d.hashes.host, d.stream));
   }
+  if (probe_off && (rc = launch_probe(p, k_tok, n_req, probe_off)) != MP_OK) return rc;
   HIP_TRY(p, hipStreamSynchronize(d.stream));
   d.hash_cache_valid = !on_device;
   d.hash_cache_n_req = n_req;
+  return MP_OK;
+}
+
+// ---- device-resident index copy ----------------------------------------------------------------
+int mirror_enable(mp_pool *p) {
+  int rc = ensure_device(p);
+  if (rc != MP_OK) return rc;
+  DeviceCtx &d = p->dev;
+  if (d.mirror_on) return MP_OK;
+  const HashTable &t = p->idx.table();
+  const uint32_t nb = p->desc.n_blocks, bs = p->desc.block_size;
+  d.mirror_cap = t.capacity();
+  if (d.mirror_cap > 0x80000000ull) return fail(p, MP_EINVAL, "pool too large for the device index copy");
+  HIP_TRY(p, hipMalloc((void **)&d.m_keys, 8ull * d.mirror_cap));
+  HIP_TRY(p, hipMalloc((void **)&d.m_vals, 4ull * d.mirror_cap));
+  HIP_TRY(p, hipMalloc((void **)&d.m_parent, 4ull * nb));
+  HIP_TRY(p, hipMalloc((void **)&d.m_tokens, 4ull * nb * bs));
+  // first copy: everything, synchronously
+  HIP_TRY(p, hipMemcpy(d.m_keys, t.keys(), 8ull * d.mirror_cap, hipMemcpyHostToDevice));
+  HIP_TRY(p, hipMemcpy(d.m_vals, t.vals(), 4ull * d.mirror_cap, hipMemcpyHostToDevice));
+  HIP_TRY(p, hipMemcpy(d.m_parent, p->idx.parents(), 4ull * nb, hipMemcpyHostToDevice));
+  HIP_TRY(p, hipMemcpy(d.m_tokens, p->idx.node_tokens(), 4ull * nb * bs, hipMemcpyHostToDevice));
+  p->idx.enable_mirror_log(true);
+  d.mirror_on = true;
+  return MP_OK;
+}
+
+void mirror_disable(mp_pool *p) {
+  DeviceCtx &d = p->dev;
+  if (!d.mirror_on) return;
+  (void)hipStreamSynchronize(d.stream);
+  p->idx.enable_mirror_log(false);
+  (void)hipFree(d.m_keys);
+  (void)hipFree(d.m_vals);
+  (void)hipFree(d.m_parent);
+  (void)hipFree(d.m_tokens);
+  d.m_keys = nullptr;
+  d.m_vals = nullptr;
+  d.m_parent = nullptr;
+  d.m_tokens = nullptr;
+  d.mirror_on = false;
+}
+
+// Brings the device copy up to date: the changed slots and nodes are written, with their
+// CURRENT host values, into pinned records that a small kernel scatters into HBM.
+int mirror_sync(mp_pool *p) {
+  DeviceCtx &d = p->dev;
+  std::vector<uint32_t> &slots = p->idx.dirty_slots();
+  std::vector<int32_t> &nodes = p->idx.dirty_nodes();
+  if (slots.empty() && nodes.empty()) return MP_OK;
+  const uint32_t bs = p->desc.block_size;
+  const HashTable &t = p->idx.table();
+  const size_t slot_dwords = 4ull * slots.size(), node_dwords = (size_t)(2 + bs) * nodes.size();
+  int rc = reserve(p, d.m_updates, 4ull * (slot_dwords + node_dwords), false);
+  if (rc != MP_OK) return rc;
+  uint32_t *u = (uint32_t *)d.m_updates.host;
+  for (size_t i = 0; i < slots.size(); ++i) {
+    const uint64_t k = t.key_at(slots[i]);
+    u[4 * i + 0] = slots[i];
+    u[4 * i + 1] = (uint32_t)t.val_at(slots[i]);
+    u[4 * i + 2] = (uint32_t)k;
+    u[4 * i + 3] = (uint32_t)(k >> 32);
+  }
+  uint32_t *nu = u + slot_dwords;
+  for (size_t i = 0; i < nodes.size(); ++i) {
+    uint32_t *r = nu + (size_t)(2 + bs) * i;
+    r[0] = (uint32_t)nodes[i];
+    r[1] = (uint32_t)p->idx.parents()[nodes[i]];
+    std::memcpy(r + 2, p->idx.node_tokens() + (size_t)nodes[i] * bs, 4ull * bs);
+  }
+  HIP_TRY(p, launch_index_apply(u, (uint32_t)slots.size(), nu, (uint32_t)nodes.size(), bs, d.m_keys,
+                                d.m_vals, d.m_parent, d.m_tokens, d.stream));
+  slots.clear();
+  nodes.clear();
+  return MP_OK;
+}
+
+// Enqueues change replay + probe.  m_out layout (pinned): [n_req+1 slot offsets][n_req matched
+// counts][ids, probe_off[n_req] of them].
+int launch_probe(mp_pool *p, const uint32_t *k_tok, uint32_t n_req, const uint32_t *probe_off) {
+  DeviceCtx &d = p->dev;
+  int rc = mirror_sync(p);
+  if (rc != MP_OK) return rc;
+  const size_t head = 2ull * n_req + 1;
+  if ((rc = reserve(p, d.m_out, 4ull * (head + probe_off[n_req]) + 4, false)) != MP_OK) return rc;
+  uint32_t *o = (uint32_t *)d.m_out.host;
+  std::memcpy(o, probe_off, 4ull * (n_req + 1));
+  const uint32_t *h_off = (const uint32_t *)d.offsets.host;
+  HIP_TRY(p, launch_index_probe(k_tok, h_off, h_off + n_req + 1, (const uint64_t *)d.hashes.host, o,
+                                n_req, p->desc.block_size, d.m_keys, d.m_vals, d.m_parent,
+                                d.m_tokens, d.mirror_cap, (int32_t *)(o + head),
+                                o + n_req + 1, d.stream));
   return MP_OK;
 }
 
@@ -662,6 +775,9 @@ int mp_pool_destroy(mp_pool_t *p) {
     release(d.tokens);
     release(d.offsets);
     release(d.hashes);
+    mirror_disable(p);
+    release(d.m_updates);
+    release(d.m_out);
     for (int s = 0; s < DeviceCtx::kTableSlots; ++s) (void)hipEventDestroy(d.tables_uploaded[s]);
     for (int s = 0; s < 2; ++s) {
       (void)hipEventDestroy(d.slot_filled[s]);
@@ -792,6 +908,30 @@ int mp_match_batch(mp_pool_t *p, const uint32_t *tokens, const uint32_t *tok_off
   std::vector<uint32_t> hoff;
   const uint32_t *htok;
   const uint64_t *hh;
+  if (p->dev.mirror_on && n_req) {
+    // device probe: slot offsets relative to the first request's slot; the host only stamps,
+    // pins and copies out what the kernel found
+    std::vector<uint32_t> rel(n_req + 1);
+    for (uint32_t r = 0; r <= n_req; ++r) rel[r] = blk_off[r] - blk_off[0];
+    int rc = device_hashes(p, tokens, tok_off, n_req, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff,
+                           &htok, &hh, rel.data());
+    if (rc != MP_OK) return rc;
+    const uint32_t *o = (const uint32_t *)p->dev.m_out.host;
+    const uint32_t *cnt = o + n_req + 1;
+    const int32_t *ids = (const int32_t *)(o + 2ull * n_req + 1);
+    for (uint32_t r = 0; r < n_req; ++r) {
+      p->idx.tick();
+      const bool any = hoff[r + 1] > hoff[r] && rel[r + 1] > rel[r];
+      const uint32_t m = any ? cnt[r] : 0;
+      int32_t *dst = blocks_out + blk_off[r];
+      if (m) std::memcpy(dst, ids + rel[r], 4ull * m);
+      p->idx.touch(dst, m);
+      if (flags & MP_MATCH_PIN)
+        for (uint32_t i = 0; i < m; ++i) p->idx.pin(dst[i]);
+      n_matched_out[r] = m;
+    }
+    return MP_OK;
+  }
   int rc = device_hashes(p, tokens, tok_off, n_req, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok,
                          &hh);
   if (rc != MP_OK) return rc;
@@ -1015,6 +1155,10 @@ int mp_set_tunable(mp_pool_t *p, const char *key, int value) {
   else if (k == "waves_per_wg" && (dflt || value == 1 || value == 4)) p->tune.waves_per_wg = value;
   else if (k == "xcd_contiguous" && (dflt || value == 0 || value == 1)) p->tune.xcd_contiguous = value;
   else if (k == "item_limit" && value >= 0) p->tune.item_limit = value;
+  else if (k == "device_probe" && (value == 0 || value == 1)) {
+    if (value) return mirror_enable(p);
+    mirror_disable(p);
+  }
   else return fail(p, MP_EINVAL, "unknown tunable or value out of range");
   return MP_OK;
 }

@@ -42,6 +42,7 @@ class HashTable {  // hash -> block id, linear probing, backward-shift deletion
     while (vals_[s] != kNoBlock) s = (s + 1) & (cap_ - 1);
     keys_[s] = h;
     vals_[s] = b;
+    if (log_) log_->push_back((uint32_t)s);
   }
   void erase(uint64_t h) {
     uint64_t s = slot(h);
@@ -55,14 +56,27 @@ class HashTable {  // hash -> block id, linear probing, backward-shift deletion
       if (!stays) {
         keys_[hole] = keys_[j];
         vals_[hole] = vals_[j];
+        if (log_) log_->push_back((uint32_t)hole);
         hole = j;
       }
     }
     vals_[hole] = kNoBlock;
+    if (log_) log_->push_back((uint32_t)hole);
   }
 
+  // A device-side copy of the table is kept current by replaying the slots logged here.
+  void set_log(std::vector<uint32_t> *log) { log_ = log; }
+  uint64_t capacity() const { return cap_; }
+  uint64_t key_at(uint64_t s) const { return keys_[s]; }
+  int32_t val_at(uint64_t s) const { return vals_[s]; }
+  const uint64_t *keys() const { return keys_.data(); }
+  const int32_t *vals() const { return vals_.data(); }
+  // home slot of a hash; the device probe uses the same function
+  static uint64_t home(uint64_t h, uint64_t cap) { return (h ^ (h >> 32)) & (cap - 1); }
+
  private:
-  uint64_t slot(uint64_t h) const { return (h ^ (h >> 32)) & (cap_ - 1); }
+  uint64_t slot(uint64_t h) const { return home(h, cap_); }
+  std::vector<uint32_t> *log_ = nullptr;
   uint64_t cap_ = 0;
   std::vector<uint64_t> keys_;
   std::vector<int32_t> vals_;
@@ -259,6 +273,7 @@ class PoolIndex {
       last_use_[b] = clock_;
       std::memcpy(&tokens_[(size_t)b * bs_], tokens + (size_t)i * bs_, 4ull * bs_);
       table_.put(hashes[i], b);
+      if (mirror_log_) dirty_nodes_.push_back(b);
       ++n_indexed_;
       if (parent != kNoBlock) {
         ++n_children_[parent];
@@ -320,6 +335,20 @@ class PoolIndex {
     return done;
   }
 
+  // ---- change log for a device-resident copy of the index ------------------------------------
+  void enable_mirror_log(bool on) {
+    mirror_log_ = on;
+    table_.set_log(on ? &dirty_slots_ : nullptr);
+    dirty_slots_.clear();
+    dirty_nodes_.clear();
+  }
+  const HashTable &table() const { return table_; }
+  std::vector<uint32_t> &dirty_slots() { return dirty_slots_; }
+  std::vector<int32_t> &dirty_nodes() { return dirty_nodes_; }
+  const int32_t *parents() const { return parent_.data(); }
+  const uint32_t *node_tokens() const { return tokens_.data(); }
+  uint32_t block_size() const { return bs_; }
+
   uint32_t node_instance(int32_t b) const { return node_instance_[b]; }
   uint32_t node_tier(int32_t b) const { return node_tier_[b]; }
 
@@ -348,6 +377,9 @@ class PoolIndex {
   HashTable table_;
   std::set<std::pair<uint64_t, int32_t>> lru_;
   std::vector<int32_t> scratch_path_;
+  bool mirror_log_ = false;
+  std::vector<uint32_t> dirty_slots_;
+  std::vector<int32_t> dirty_nodes_;
 };
 
 }  // namespace mempool

@@ -281,8 +281,8 @@ def test_tiny_config_walkthrough(gpu):
     dg.close()
 
 
-@pytest.mark.parametrize("seed", [0, 1, 2])
-def test_random_workflow_against_oracle(gpu, seed):
+@pytest.mark.parametrize("seed,probe", [(0, 0), (1, 0), (2, 0), (0, 1), (3, 1), (4, 1)])
+def test_random_workflow_against_oracle(gpu, seed, probe):
     """Random interleaving of match / transfer_with_insert / free / evict on a small, tight
     destination pool: ids, index answers, statistics and every pool byte must agree."""
     M, TorchPool = gpu
@@ -291,6 +291,7 @@ def test_random_workflow_against_oracle(gpu, seed):
     rng = np.random.default_rng(100 + seed)
     so, sg = make_pair(gpu, geom, 64, seed, staging_blocks=5)
     do, dg = make_pair(gpu, geom, 24, seed + 50, staging_blocks=0, hash_seed=seed)
+    assert M.mp_set_tunable(dg.h, "device_probe", probe) == 0    # index walk on the GPU or on the host
     M.mp_alloc(sg.h, 64)
     so.alloc(64)
     prompts, live = [], []
@@ -367,13 +368,15 @@ def test_stale_prefix_and_given_destinations(gpu):
     dg.close()
 
 
-def test_batched_forms(gpu):
+@pytest.mark.parametrize("probe", [0, 1])
+def test_batched_forms(gpu, probe):
     M, TorchPool = gpu
     geom = GEOMS["tiny"]
     bs = geom[3]
     rng = np.random.default_rng(12)
     so, sg = make_pair(gpu, geom, 96, 3, staging_blocks=7)       # several staging rounds
     do, dg = make_pair(gpu, geom, 200, 4, staging_blocks=0)
+    assert M.mp_set_tunable(dg.h, "device_probe", probe) == 0
     M.mp_alloc(sg.h, 96)
     so.alloc(96)
     shared = rng.integers(0, 32000, 3 * bs, dtype=np.uint32)
@@ -583,6 +586,8 @@ def test_mixed_features_random(gpu, seed):
     do, dg = make_pair(gpu, geom, int(rng.integers(16, 40)), seed + 50,
                        staging_blocks=int(rng.integers(1, 5)), hash_seed=seed, layout=lay_d)
     ho, hg = make_pair(gpu, geom, 24, seed + 70, staging_blocks=0, tier=1, hash_seed=seed)
+    for p in (dg, hg):
+        assert M.mp_set_tunable(p.h, "device_probe", seed % 2) == 0
     M.mp_alloc(sg.h, 64)
     so.alloc(64)
     prompts, live, hlive = [], [], []
@@ -644,3 +649,42 @@ def test_mixed_features_random(gpu, seed):
         _same_state(ho, hg)
     for p in (sg, dg, hg):
         p.close()
+
+
+def test_device_probe_switched_on_late_and_long_prompts(gpu):
+    """The device copy of the index is seeded from a populated index, follows inserts, evictions
+    and deletes, and handles prompts longer than one probe tile (1024 blocks)."""
+    M, TorchPool = gpu
+    geom = (1, 1, 8, 2, 2)                       # bs = 2: long chains from few tokens
+    bs = 2
+    NB = 6000
+    o = O.OraclePool(*geom, NB)
+    g = TorchPool(*geom, NB)
+    rng = np.random.default_rng(31)
+    long_a = rng.integers(0, 5, 2 * 2500, dtype=np.uint32)           # 2500 blocks
+    long_b = np.concatenate([long_a[: 2 * 1500], rng.integers(0, 5, 2 * 700 + 1, dtype=np.uint32)])
+    for t in (long_a, long_b):
+        nb = len(t) // bs
+        rc, ids = M.mp_alloc(g.h, nb)
+        _, ids_o = o.alloc(nb)
+        assert M.mp_insert(g.h, t, ids) == o.insert(t, ids_o)
+        assert M.mp_free(g.h, ids) == o.free(ids_o) == 0
+    assert M.mp_set_tunable(g.h, "device_probe", 1) == 0             # seeded from the live index
+    for t in (long_a, long_b, long_a[: 2 * 1024], long_a[: 2 * 1025 + 1], long_b[:3], np.zeros(0, np.uint32)):
+        nb = len(t) // bs
+        assert M.mp_match(g.h, t, nb)[1].tolist() == o.match(t)[1].tolist()
+        assert M.mp_match(g.h, t, max(nb - 3, 0))[1].tolist() == o.match(t, cap=max(nb - 3, 0))[1].tolist()
+    assert M.mp_delete(g.h, long_b) == o.delete(long_b)
+    assert M.mp_evict(g.h, 900) == o.evict(900)
+    for t in (long_a, long_b):
+        assert M.mp_match(g.h, t, len(t) // bs)[1].tolist() == o.match(t)[1].tolist()
+    # a hash that is in the table but with other tokens (forged via the *_hashed entry) stays a miss
+    t2 = long_a[: 2 * 4].copy()
+    rc, h2 = M.mp_block_hashes(g.h, t2, bs)
+    t2[0] ^= 1
+    rc, ids = M.mp_alloc(g.h, 0)
+    assert M.mp_match(g.h, t2, 4)[1].tolist() == o.match(t2)[1].tolist()
+    assert g.stats() == o.stats()
+    assert M.mp_set_tunable(g.h, "device_probe", 0) == 0
+    assert M.mp_match(g.h, long_a, 2500)[1].tolist() == o.match(long_a)[1].tolist()
+    g.close()
