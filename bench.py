@@ -222,6 +222,50 @@ def host_tier(args):
     host.close()
 
 
+def per_fragment_reference(args):
+    """Reference point: the same small transfer as one copy-engine call per discrete fragment
+    (the paper's one-network-call-per-block pattern, its "Original" layout) against one launch
+    per direction (staged) and one fused launch."""
+    import torch
+    from paper_2406_17565_amd import mempool as M
+    from paper_2406_17565_amd import workloads as W
+    from paper_2406_17565_amd.pool import TorchPool
+    out = {"metric": "per-fragment copy calls vs one launch, KV transfer GB/s", "unit": "GB/s",
+           "n_gpus": 1, "dtype": "u8", "data": "synthetic", "rows": []}
+    for cfg, n in ((3, 64), (5, 64)):
+        g = W.CONFIGS[cfg]
+        geom = (g.L, g.H, g.D, g.bs, g.e)
+        NB = 2048
+        src = TorchPool(*geom, NB, staging_blocks=n)
+        dst = TorchPool(*geom, NB)
+        src.mem.view(torch.int32).random_()
+        torch.cuda.synchronize()
+        M.mp_alloc(src.h, NB)
+        rc, d = M.mp_alloc(dst.h, n)
+        rng = np.random.default_rng(cfg)
+        row = {"config": cfg, "blocks": n, "fragments": n * 2 * g.L, "fragment_bytes": g.F,
+               "payload_MiB": round(n * g.B / 2**20, 1)}
+        for name, fl in (("per_fragment_calls", M.MP_PER_FRAGMENT), ("staged_two_launches", 0),
+                         ("fused_one_launch", M.MP_DIRECT)):
+            ts = []
+            for _ in range(6):
+                tbl = rng.permutation(NB)[:n].astype(np.int32)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                rc, _ = M.mp_transfer(src.h, dst.h, tbl, d, flags=fl | M.MP_DST_GIVEN)
+                ts.append(time.perf_counter() - t0)
+                assert rc == 0, M.mp_last_error(src.h)
+            t = min(ts[1:])
+            row[name] = {"GBs": round(n * g.B / t / 1e9, 2), "us": round(t * 1e6, 1),
+                         "us_per_fragment": round(t * 1e6 / (n * 2 * g.L), 3)}
+        out["rows"].append(row)
+        src.close()
+        dst.close()
+        del src, dst
+        torch.cuda.empty_cache()
+    print(json.dumps(out))
+
+
 def api_latency(args):
     """Latency of the control-plane calls, next to the paper's API study (section 8.4: about
     800 ns per block for the memory APIs, at most 0.7 ms to insert a 4K-token prompt of 256
@@ -323,6 +367,8 @@ def main():
                     help="ship one layer per call (mp_transfer_layers) instead of whole blocks")
     ap.add_argument("--host-tier", action="store_true", help="config 5 HBM <-> pinned-host variant")
     ap.add_argument("--api-latency", action="store_true", help="latency of the control-plane calls")
+    ap.add_argument("--per-fragment", action="store_true",
+                    help="reference point: one copy call per discrete fragment vs one launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--tune", default="", help="comma list key=value for mp_set_tunable")
     args = ap.parse_args()
@@ -335,6 +381,8 @@ def main():
         return host_tier(args)
     if args.api_latency:
         return api_latency(args)
+    if args.per_fragment:
+        return per_fragment_reference(args)
     if args.steps is None:
         args.steps = {2: 8, 3: 20, 4: 32, 5: 6}[args.config]
     if args.warmup is None:

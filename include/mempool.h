@@ -87,6 +87,9 @@ typedef struct mp_pool mp_pool_t; /* opaque, library-owned */
 #define MP_ASYNC 0x04u            /* enqueue only; results valid in stream order              */
 #define MP_MATCH_PIN 0x08u        /* mp_match: take one reference on every returned block     */
 #define MP_TOKENS_ON_DEVICE 0x10u /* `tokens` is a device pointer (same device as the pool)   */
+#define MP_PER_FRAGMENT 0x40u     /* reference point only: one copy-engine call per discrete
+                                     fragment (2*L per block), the one-call-per-block pattern
+                                     the paper measures as "Original" (sections 5.2, 8.4)     */
 #define MP_DIRECT 0x20u           /* one fused kernel, no staging round trip; with a pinned-host
                                      pool at one end the kernel accesses host memory itself  */
 
@@ -159,6 +162,13 @@ int mp_evict(mp_pool_t *p, uint32_t n_blocks, uint32_t *n_evicted_out);
 int mp_transfer(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks,
                 int32_t *dst_blocks /* in with MP_DST_GIVEN, else out */, uint32_t n,
                 uint32_t flags, const void *priv, uint64_t priv_len);
+
+/* transfer for n_req requests at once: request r owns entries blk_off[r] .. blk_off[r+1] of both
+ * tables.  The data plane never needs the request boundaries (one launch covers the whole
+ * table), so this is mp_transfer over blk_off[n_req] entries after the offsets are checked. */
+int mp_transfer_batch(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks,
+                      int32_t *dst_blocks, const uint32_t *blk_off, uint32_t n_req,
+                      uint32_t flags);
 
 /* By-layer transfer (section 4.3: an explicit destination list "is particularly useful for
  * constructing layer-by-layer transmissions"; section 5.2: by-layer vs by-request): copies only

@@ -450,7 +450,7 @@ int check_copy_feasible(mp_pool *src, mp_pool *dst, uint32_t n, uint32_t flags,
                         uint32_t n_layers = 0 /* 0 = all */) {
   const bool s_hbm = src->desc.tier == MP_TIER_HBM, d_hbm = dst->desc.tier == MP_TIER_HBM;
   if (!s_hbm && !d_hbm) return fail(src, MP_ESHAPE, "host-to-host transfers are not supported");
-  if (flags & MP_DIRECT) return MP_OK;  // no staging: the kernel addresses both pools itself
+  if (flags & (MP_DIRECT | MP_PER_FRAGMENT)) return MP_OK;  // no staging involved
   if (n_layers && (!s_hbm || !d_hbm))
     return fail(src, MP_ESHAPE, "a by-layer transfer with a host-tier pool needs MP_DIRECT");
   if (n == 0) return MP_OK;
@@ -478,9 +478,25 @@ int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *
   const uint64_t B = (uint64_t)planes * x->F;  // bytes moved per table entry
   const int32_t *d_src = nullptr, *d_dst = nullptr;
   const bool direct = (flags & MP_DIRECT) != 0;
-  rc = upload_tables(x, (s_hbm || direct) ? src_ids : nullptr, (d_hbm || direct) ? dst_ids : nullptr,
-                     n, &d_src, &d_dst);
-  if (rc != MP_OK) return rc;
+  if (!(flags & MP_PER_FRAGMENT)) {
+    rc = upload_tables(x, (s_hbm || direct) ? src_ids : nullptr, (d_hbm || direct) ? dst_ids : nullptr,
+                       n, &d_src, &d_dst);
+    if (rc != MP_OK) return rc;
+  }
+
+  if (flags & MP_PER_FRAGMENT) {
+    // Reference point, not a product path: one copy-engine call per discrete fragment, the way
+    // a per-block network API moves a paged KV cache (paper sections 5.2 and 7).
+    for (uint32_t i = 0; i < n; ++i)
+      for (uint32_t pl = 0; pl < planes; ++pl) {
+        const CopySide s = pool_side(src, nullptr, l0), t = pool_side(dst, nullptr, l0);
+        const uint8_t *from = (const uint8_t *)s.base + pl * s.plane_stride +
+                              (uint64_t)src_ids[i] * s.block_stride;
+        uint8_t *to = (uint8_t *)t.base + pl * t.plane_stride + (uint64_t)dst_ids[i] * t.block_stride;
+        HIP_TRY(x, hipMemcpyAsync(to, from, x->F, hipMemcpyDefault, d.stream));
+      }
+    return MP_OK;
+  }
 
   if (direct) {
     // One fused kernel, fragment to fragment.  With a pinned-host pool at one end the kernel
@@ -1003,6 +1019,17 @@ int mp_transfer(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks, int32
   if (rc != MP_OK) return rc;
   if (dst->cb) dst->cb(dst->cb_user, priv, priv_len, dst_blocks, n);
   return MP_OK;
+}
+
+int mp_transfer_batch(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks,
+                      int32_t *dst_blocks, const uint32_t *blk_off, uint32_t n_req,
+                      uint32_t flags) {
+  if (!src || !dst) return MP_EINVAL;
+  if (!blk_off) return fail(src, MP_EINVAL, "null offsets");
+  if (blk_off[0] != 0) return fail(src, MP_EINVAL, "offsets must start at 0");
+  for (uint32_t r = 0; r < n_req; ++r)
+    if (blk_off[r + 1] < blk_off[r]) return fail(src, MP_EINVAL, "offsets must be non-decreasing");
+  return mp_transfer(src, dst, src_blocks, dst_blocks, blk_off[n_req], flags, nullptr, 0);
 }
 
 int mp_transfer_layers(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks,

@@ -17,6 +17,7 @@ MP_LAYOUT_DEFAULT, MP_LAYOUT_DISCRETE, MP_LAYOUT_AGGREGATED = 0, 1, 2
 MP_OK, MP_EINVAL, MP_ESHAPE, MP_ENOMEM, MP_ENOSTAGING, MP_EHIP, MP_ESTALE = 0, -1, -2, -3, -4, -5, -6
 MP_DST_GIVEN, MP_EVICT_ON_DEMAND, MP_ASYNC = 0x01, 0x02, 0x04
 MP_MATCH_PIN, MP_TOKENS_ON_DEVICE, MP_DIRECT = 0x08, 0x10, 0x20
+MP_PER_FRAGMENT = 0x40
 PROF_GATHER, PROF_SCATTER, PROF_DIRECT, PROF_HASH = 0, 1, 2, 3
 
 EXPORTS = [
@@ -26,7 +27,7 @@ EXPORTS = [
     "mp_block_hashes", "mp_insert_hashed", "mp_match_hashed", "mp_gather", "mp_scatter",
     "mp_set_recv_callback", "mp_profile_enable", "mp_profile_read", "mp_set_tunable",
     "mp_selftest", "mp_plain_copy", "mp_transfer_layers",
-    "mp_block_hashes_batch", "mp_delete", "mp_delete_hashed",
+    "mp_block_hashes_batch", "mp_delete", "mp_delete_hashed", "mp_transfer_batch",
 ]
 
 
@@ -75,6 +76,7 @@ def lib():
             "mp_transfer": [vp, vp, vp, vp, u32, u32, vp, u64],
             "mp_transfer_with_insert": [vp, vp, vp, u32, u32, vp, vp, u32, u32, vp, u64],
             "mp_transfer_layers": [vp, vp, vp, vp, u32, u32, u32, u32],
+            "mp_transfer_batch": [vp, vp, vp, vp, vp, u32, u32],
             "mp_match_batch": [vp, vp, vp, u32, vp, vp, vp, u32],
             "mp_transfer_with_insert_batch": [vp, vp, vp, vp, u32, vp, vp, vp, vp, u32],
             "mp_block_hashes": [vp, vp, u32, vp, u32],
@@ -208,6 +210,13 @@ def mp_transfer(src, dst, src_blocks, dst_blocks=None, flags=0, priv=b""):
     s = _i32(src_blocks)
     d = _i32(dst_blocks).copy() if dst_blocks is not None else np.full(s.size, -1, dtype=np.int32)
     rc = lib().mp_transfer(src, dst, _ptr(s), _ptr(d), s.size, flags, priv or None, len(priv))
+    return rc, d
+
+
+def mp_transfer_batch(src, dst, src_blocks, blk_off, dst_blocks=None, flags=0):
+    s, bo = _i32(src_blocks), _u32(blk_off)
+    d = _i32(dst_blocks).copy() if dst_blocks is not None else np.full(s.size, -1, dtype=np.int32)
+    rc = lib().mp_transfer_batch(src, dst, _ptr(s), _ptr(d), bo.ctypes.data, bo.size - 1, flags)
     return rc, d
 
 

@@ -207,6 +207,16 @@ def test_transfer_and_errors(gpu, mode):
     other = TorchPool(3, 5, 24, 2, 2, 8)
     assert M.mp_transfer(sg.h, other.h, [1])[0] == M.MP_ESHAPE
     assert np.array_equal(dg.bytes(), snap) and dg.stats() == st
+    # batched form and the one-call-per-fragment reference point give the same bytes
+    tb = rng.integers(0, 40, 5).astype(np.int32)
+    rc, db = M.mp_transfer_batch(sg.h, dg.h, tb, [0, 2, 2, 5], flags=flags)
+    rco, db_o = O.transfer(so, do, tb)
+    assert rc == rco == 0 and db.tolist() == db_o.tolist()
+    rc, _ = M.mp_transfer(sg.h, dg.h, tb[::-1].copy(), db, flags=M.MP_PER_FRAGMENT | M.MP_DST_GIVEN)
+    rco, _ = O.transfer(so, do, tb[::-1].copy(), db_o, flags=O.DST_GIVEN)
+    assert rc == rco == 0
+    _same_state(do, dg)
+    assert M.mp_transfer_batch(sg.h, dg.h, tb, [1, 5], flags=flags)[0] == M.MP_EINVAL
     # n = 0
     rc, d0 = M.mp_transfer(sg.h, dg.h, np.zeros(0, np.int32), flags=flags)
     assert rc == 0 and d0.size == 0

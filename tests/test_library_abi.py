@@ -43,7 +43,7 @@ def test_header_constants_match_binding():
         m = re.search(rf"#define {name} \((-\d+)\)", text)
         assert int(m.group(1)) == getattr(M, name)
     for name in ("MP_DST_GIVEN", "MP_EVICT_ON_DEMAND", "MP_ASYNC", "MP_MATCH_PIN",
-                 "MP_TOKENS_ON_DEVICE", "MP_DIRECT"):
+                 "MP_TOKENS_ON_DEVICE", "MP_DIRECT", "MP_PER_FRAGMENT"):
         m = re.search(rf"#define {name} (0x[0-9a-f]+)u", text)
         assert int(m.group(1), 16) == getattr(M, name)
 
