@@ -97,7 +97,6 @@ struct mp_pool {
   std::string err;
   mp_recv_cb cb = nullptr;
   void *cb_user = nullptr;
-  std::vector<uint64_t> host_hashes;  // scratch
   std::vector<int32_t> scratch_ids;
 };
 
@@ -435,8 +434,6 @@ CopySide record_side(const mp_pool *p, void *base, uint32_t planes) {
   return s;
 }
 
-CopyTune effective_tune(const mp_pool *p) { return p->tune; }
-
 bool tables_overlap(const mp_pool *p, const int32_t *a, const int32_t *b, uint32_t n) {
   std::vector<uint8_t> seen(p->desc.n_blocks, 0);
   for (uint32_t i = 0; i < n; ++i) seen[a[i]] = 1;
@@ -474,7 +471,7 @@ int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *
   int rc = ensure_device(x);
   if (rc != MP_OK) return rc;
   DeviceCtx &d = x->dev;
-  const CopyTune tune = effective_tune(x);
+  const CopyTune tune = x->tune;
   const uint64_t B = (uint64_t)planes * x->F;  // bytes moved per table entry
   const int32_t *d_src = nullptr, *d_dst = nullptr;
   const bool direct = (flags & MP_DIRECT) != 0;
@@ -1091,7 +1088,7 @@ int mp_gather(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags) {
   {
     ProfScope ps(p, kProfGather, 2ull * n * p->B);
     HIP_TRY(p, launch_block_copy(pool_side(p, d_src), record_side(p, p->desc.staging, p->P), n, p->P,
-                                 p->F, effective_tune(p), p->dev.n_cus, p->dev.stream));
+                                 p->F, p->tune, p->dev.n_cus, p->dev.stream));
   }
   if (!(flags & MP_ASYNC)) HIP_TRY(p, hipStreamSynchronize(p->dev.stream));
   return MP_OK;
@@ -1117,7 +1114,7 @@ int mp_scatter(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags) {
   {
     ProfScope ps(p, kProfScatter, 2ull * n * p->B);
     HIP_TRY(p, launch_block_copy(record_side(p, p->desc.staging, p->P), pool_side(p, d_dst), n, p->P,
-                                 p->F, effective_tune(p), p->dev.n_cus, p->dev.stream));
+                                 p->F, p->tune, p->dev.n_cus, p->dev.stream));
   }
   if (!(flags & MP_ASYNC)) HIP_TRY(p, hipStreamSynchronize(p->dev.stream));
   return MP_OK;
