@@ -520,6 +520,38 @@ def main():
     _, h_ms, h_n, h_bytes = M.mp_profile_read(dst.h, M.PROF_HASH)
     achieved = k_bytes / (k_ms * 1e-3) / 1e9 if k_ms else 0.0
 
+    # the same workload once more with the fused pool-to-pool kernel (half the HBM traffic), as a
+    # second figure next to the headline; not part of the timed K steps above
+    fused = None
+    if args.config == 3 and not (args.direct or args.per_request or args.by_layer):
+        for ids in state["held"]:
+            assert M.mp_free(dst.h, ids) == 0
+        state["held"].clear()
+        n_extra = 2 * n_turns
+        extra = [build_epoch(W, geom, args.config, n_epochs + k) for k in range(2)]
+        f_flags = flags | M.MP_DIRECT
+        f_moved, f_t0 = 0, None
+        for j in range(n_extra):
+            if j == n_turns:                   # first extra epoch = warm-up of the fused path
+                torch.cuda.synchronize()
+                M.mp_profile_read(src.h, M.PROF_DIRECT)
+                f_t0 = time.perf_counter()
+            mv = run_step(M, src, dst, extra[j // n_turns][j % n_turns],
+                          rng.permutation(NB_src).astype(np.int32), state, f_flags)
+            if j >= n_turns:
+                f_moved += mv
+            if j % n_turns == n_turns - 1:
+                for ids in state["held"]:
+                    assert M.mp_free(dst.h, ids) == 0
+                state["held"].clear()
+        torch.cuda.synchronize()
+        f_dt = time.perf_counter() - f_t0
+        _, f_ms, f_n, f_bytes = M.mp_profile_read(src.h, M.PROF_DIRECT)
+        fused = {"value": round(f_moved * geom.B / f_dt / 1e9, 2), "unit": "GB/s",
+                 "ms_per_step": round(f_dt / n_turns * 1e3, 4), "steps": n_turns,
+                 "kernel_GBs": round(f_bytes / (f_ms * 1e-3) / 1e9, 1) if f_ms else None,
+                 "path": "direct (fused pool->pool, MP_DIRECT)"}
+
     # measured HBM traffic per algorithmic byte, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
     # whose summary is committed under profiles/ (counters cannot be read from inside this run)
     traffic = traffic_src = None
@@ -590,6 +622,8 @@ def main():
                              for k, v in per_kind.items()},
         },
     }
+    if fused:
+        out["fused"] = fused
     if not args.no_cpu_baseline and args.config == 3:
         out["cpu_baseline"] = cpu_baseline(W, geom)
     print(json.dumps(out))
