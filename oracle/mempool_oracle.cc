@@ -293,11 +293,15 @@ void orc_stats(const orc_pool_t *p, uint32_t *n_free, uint32_t *n_held, uint32_t
   *n_held = held; *n_indexed = idx; *n_historical = hist; *clock = p->clock;
 }
 
+// alloc_mem (Table 1: "alloc a certain type of memory ..., return addrList"); the table's
+// caption allows on-demand allocation, here: eviction of the shortfall when the flag asks.
 int orc_alloc(orc_pool_t *p, uint32_t n, int32_t *out, uint32_t flags) {
   if (!p || (!out && n)) return ORC_EINVAL;
   return alloc_blocks(p, n, out, flags);
 }
 
+// free_mem (Table 1).  A block that the index still maps stays resident as historical KV
+// (section 4.1: active vs historical cache) until it is evicted or deleted.
 int orc_free(orc_pool_t *p, const int32_t *blocks, uint32_t n) {
   if (!p || (!blocks && n)) return ORC_EINVAL;
   std::map<int32_t, uint32_t> times;
@@ -312,6 +316,8 @@ int orc_free(orc_pool_t *p, const int32_t *blocks, uint32_t n) {
   return ORC_OK;
 }
 
+// insert (Table 1: "insert prompt token and KV cache address mapping into local index");
+// granularity = the engine's block (section 4.2, last paragraph).
 int orc_insert(orc_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, const int32_t *blocks,
                uint32_t n_blocks, uint32_t *n_new) {
   if (!p || (!tokens && n_tokens) || !n_new) return ORC_EINVAL;
@@ -324,6 +330,8 @@ int orc_insert(orc_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, const i
   return ORC_OK;
 }
 
+// match (Table 1: "find prompt's cached data if any, return addrList"): the longest indexed
+// block-aligned prefix.
 int orc_match(orc_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, int32_t *blocks_out,
               uint32_t cap, uint32_t *n_matched, uint32_t flags) {
   if (!p || (!tokens && n_tokens) || !n_matched || (!blocks_out && cap)) return ORC_EINVAL;
@@ -361,6 +369,7 @@ int orc_delete(orc_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, uint32_
   return ORC_OK;
 }
 
+// evict (named among the index APIs in Table 3 only; the policy is this build's convention).
 int orc_evict(orc_pool_t *p, uint32_t k, uint32_t *n_evicted) {
   if (!p || !n_evicted) return ORC_EINVAL;
   uint32_t done = 0;
@@ -433,6 +442,10 @@ int orc_transfer_layers(orc_pool_t *src, orc_pool_t *dst, const int32_t *src_blo
   return ORC_OK;
 }
 
+// transfer_with_insert (Table 1; section 4.3: after the data has arrived the receiver inserts
+// the prompt into its own index, which saves a round trip).  Blocks [0, first_block) are the
+// part of the prompt the receiver already holds (section 5.1: with a cache at the receiver only
+// the new KV moves).
 int orc_transfer_with_insert(orc_pool_t *src, orc_pool_t *dst, const uint32_t *tokens,
                              uint32_t n_tokens, uint32_t first_block,
                              const int32_t *src_blocks, int32_t *dst_blocks, uint32_t n,
