@@ -39,7 +39,7 @@
  *
  * ERRORS
  *   Every call returns MP_OK (0) or a negative code.  Calls are all-or-nothing: when a code
- *   other than MP_OK or MP_EHIP comes back, no pool byte, index entry, reference count or
+ *   other than MP_OK, MP_EHIP or MP_EHOST comes back, no pool byte, index entry, reference count or
  *   free-list entry has changed.  mp_last_error(pool) returns a text for the last failure.
  *
  * THREADS AND STREAMS
@@ -80,6 +80,7 @@ typedef struct mp_pool mp_pool_t; /* opaque, library-owned */
 #define MP_ENOSTAGING (-4) /* staging buffer missing or smaller than what the call needs */
 #define MP_EHIP (-5)       /* a HIP runtime call failed */
 #define MP_ESTALE (-6)     /* transfer_with_insert: blocks [0,first_block) not in dst index */
+#define MP_EHOST (-7)      /* host memory allocation failed / internal error (state undefined) */
 
 /* flags (bitmask) */
 #define MP_DST_GIVEN 0x01u        /* caller supplies dst_blocks; allocation step skipped      */

@@ -15,6 +15,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -112,6 +113,16 @@ int fail_hip(mp_pool *p, hipError_t e, const char *where) {
   return MP_EHIP;
 }
 
+// No C++ exception may cross the C ABI: every entry point that can allocate host memory
+// turns a failure into MP_EHOST.
+#define MP_CATCH(pool)                                                        \
+  catch (const std::bad_alloc &) {                                            \
+    return fail(pool, MP_EHOST, "out of host memory");                        \
+  }                                                                           \
+  catch (...) {                                                               \
+    return fail(pool, MP_EHOST, "unexpected internal error");                 \
+  }
+
 #define HIP_TRY(pool, expr)                                  \
   do {                                                       \
     hipError_t e_ = (expr);                                  \
@@ -130,9 +141,22 @@ bool same_geometry(const mp_pool *a, const mp_pool *b) {
 }
 
 // ---- device context ----------------------------------------------------------------------
-int ensure_device(mp_pool *p) {
+void destroy_device_objects(DeviceCtx &d) {
+  if (d.side) (void)hipStreamDestroy(d.side);
+  d.side = nullptr;
+  for (int s = 0; s < DeviceCtx::kTableSlots; ++s) {
+    if (d.tables_uploaded[s]) (void)hipEventDestroy(d.tables_uploaded[s]);
+    d.tables_uploaded[s] = nullptr;
+  }
+  for (int s = 0; s < 2; ++s) {
+    if (d.slot_filled[s]) (void)hipEventDestroy(d.slot_filled[s]);
+    if (d.slot_drained[s]) (void)hipEventDestroy(d.slot_drained[s]);
+    d.slot_filled[s] = d.slot_drained[s] = nullptr;
+  }
+}
+
+int create_device_objects(mp_pool *p) {
   DeviceCtx &d = p->dev;
-  if (d.ready) return MP_OK;
   HIP_TRY(p, hipGetDevice(&d.device));
   int cus = 0;
   HIP_TRY(p, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, d.device));
@@ -144,6 +168,19 @@ int ensure_device(mp_pool *p) {
   for (int s = 0; s < 2; ++s) {
     HIP_TRY(p, hipEventCreateWithFlags(&d.slot_filled[s], hipEventDisableTiming));
     HIP_TRY(p, hipEventCreateWithFlags(&d.slot_drained[s], hipEventDisableTiming));
+  }
+  return MP_OK;
+}
+
+// Streams and events are created at the first call that needs the device, so that the
+// control-plane calls work without a GPU.
+int ensure_device(mp_pool *p) {
+  DeviceCtx &d = p->dev;
+  if (d.ready) return MP_OK;
+  const int rc = create_device_objects(p);
+  if (rc != MP_OK) {
+    destroy_device_objects(d);  // nothing half-made is kept
+    return rc;
   }
   d.ready = true;
   return MP_OK;
@@ -279,6 +316,17 @@ int device_hashes(mp_pool *p, const uint32_t *tokens, const uint32_t *tok_off, u
 }
 
 // ---- device-resident index copy ----------------------------------------------------------------
+void free_mirror_arrays(DeviceCtx &d) {
+  if (d.m_keys) (void)hipFree(d.m_keys);
+  if (d.m_vals) (void)hipFree(d.m_vals);
+  if (d.m_parent) (void)hipFree(d.m_parent);
+  if (d.m_tokens) (void)hipFree(d.m_tokens);
+  d.m_keys = nullptr;
+  d.m_vals = nullptr;
+  d.m_parent = nullptr;
+  d.m_tokens = nullptr;
+}
+
 int mirror_enable(mp_pool *p) {
   int rc = ensure_device(p);
   if (rc != MP_OK) return rc;
@@ -288,15 +336,20 @@ int mirror_enable(mp_pool *p) {
   const uint32_t nb = p->desc.n_blocks, bs = p->desc.block_size;
   d.mirror_cap = t.capacity();
   if (d.mirror_cap > 0x80000000ull) return fail(p, MP_EINVAL, "pool too large for the device index copy");
-  HIP_TRY(p, hipMalloc((void **)&d.m_keys, 8ull * d.mirror_cap));
-  HIP_TRY(p, hipMalloc((void **)&d.m_vals, 4ull * d.mirror_cap));
-  HIP_TRY(p, hipMalloc((void **)&d.m_parent, 4ull * nb));
-  HIP_TRY(p, hipMalloc((void **)&d.m_tokens, 4ull * nb * bs));
+  hipError_t e = hipMalloc((void **)&d.m_keys, 8ull * d.mirror_cap);
+  if (e == hipSuccess) e = hipMalloc((void **)&d.m_vals, 4ull * d.mirror_cap);
+  if (e == hipSuccess) e = hipMalloc((void **)&d.m_parent, 4ull * nb);
+  if (e == hipSuccess) e = hipMalloc((void **)&d.m_tokens, 4ull * nb * bs);
   // first copy: everything, synchronously
-  HIP_TRY(p, hipMemcpy(d.m_keys, t.keys(), 8ull * d.mirror_cap, hipMemcpyHostToDevice));
-  HIP_TRY(p, hipMemcpy(d.m_vals, t.vals(), 4ull * d.mirror_cap, hipMemcpyHostToDevice));
-  HIP_TRY(p, hipMemcpy(d.m_parent, p->idx.parents(), 4ull * nb, hipMemcpyHostToDevice));
-  HIP_TRY(p, hipMemcpy(d.m_tokens, p->idx.node_tokens(), 4ull * nb * bs, hipMemcpyHostToDevice));
+  if (e == hipSuccess) e = hipMemcpy(d.m_keys, t.keys(), 8ull * d.mirror_cap, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(d.m_vals, t.vals(), 4ull * d.mirror_cap, hipMemcpyHostToDevice);
+  if (e == hipSuccess) e = hipMemcpy(d.m_parent, p->idx.parents(), 4ull * nb, hipMemcpyHostToDevice);
+  if (e == hipSuccess)
+    e = hipMemcpy(d.m_tokens, p->idx.node_tokens(), 4ull * nb * bs, hipMemcpyHostToDevice);
+  if (e != hipSuccess) {
+    free_mirror_arrays(d);
+    return fail_hip(p, e, "device index copy");
+  }
   p->idx.enable_mirror_log(true);
   d.mirror_on = true;
   return MP_OK;
@@ -307,14 +360,7 @@ void mirror_disable(mp_pool *p) {
   if (!d.mirror_on) return;
   (void)hipStreamSynchronize(d.stream);
   p->idx.enable_mirror_log(false);
-  (void)hipFree(d.m_keys);
-  (void)hipFree(d.m_vals);
-  (void)hipFree(d.m_parent);
-  (void)hipFree(d.m_tokens);
-  d.m_keys = nullptr;
-  d.m_vals = nullptr;
-  d.m_parent = nullptr;
-  d.m_tokens = nullptr;
+  free_mirror_arrays(d);
   d.mirror_on = false;
 }
 
@@ -726,6 +772,7 @@ const char *mp_strerror(int code) {
     case MP_ENOSTAGING: return "staging buffer missing or too small";
     case MP_EHIP: return "HIP runtime error";
     case MP_ESTALE: return "claimed prefix not in destination index";
+    case MP_EHOST: return "host memory allocation failed or internal error";
     default: return "unknown error";
   }
 }
@@ -755,26 +802,29 @@ int mp_selftest(void) {
 }
 
 int mp_pool_create(const mp_pool_desc_t *desc, mp_pool_t **out) {
-  if (!desc || !out) return MP_EINVAL;
-  *out = nullptr;
-  if (!desc->n_layers || !desc->n_kv_heads || !desc->head_dim || !desc->block_size ||
-      !desc->elem_bytes || !desc->n_blocks || !desc->base)
-    return MP_EINVAL;
-  if (desc->tier != MP_TIER_HBM && desc->tier != MP_TIER_HOST_PINNED) return MP_EINVAL;
-  if (desc->layout > MP_LAYOUT_AGGREGATED || desc->reserved != 0) return MP_EINVAL;
-  if (desc->tier == MP_TIER_HOST_PINNED && desc->layout == MP_LAYOUT_DISCRETE) return MP_EINVAL;
-  if (desc->n_blocks > 0x7fffffffu || desc->n_layers > 0x7fffu) return MP_EINVAL;
-  const uint64_t F = (uint64_t)desc->block_size * desc->n_kv_heads * desc->head_dim * desc->elem_bytes;
-  if (F % 16 != 0 || F > (1ull << 34)) return MP_EINVAL;
-  if (((uintptr_t)desc->base & 15u) || ((uintptr_t)desc->staging & 15u)) return MP_EINVAL;
-  mp_pool *p = new mp_pool;
-  p->desc = *desc;
-  p->F = F;
-  p->P = 2 * desc->n_layers;
-  p->B = F * p->P;
-  p->idx.init(desc->n_blocks, desc->block_size, desc->tier, desc->instance_id);
-  *out = p;
-  return MP_OK;
+  try {
+    if (!desc || !out) return MP_EINVAL;
+    *out = nullptr;
+    if (!desc->n_layers || !desc->n_kv_heads || !desc->head_dim || !desc->block_size ||
+        !desc->elem_bytes || !desc->n_blocks || !desc->base)
+      return MP_EINVAL;
+    if (desc->tier != MP_TIER_HBM && desc->tier != MP_TIER_HOST_PINNED) return MP_EINVAL;
+    if (desc->layout > MP_LAYOUT_AGGREGATED || desc->reserved != 0) return MP_EINVAL;
+    if (desc->tier == MP_TIER_HOST_PINNED && desc->layout == MP_LAYOUT_DISCRETE) return MP_EINVAL;
+    if (desc->n_blocks > 0x7fffffffu || desc->n_layers > 0x7fffu) return MP_EINVAL;
+    const uint64_t F = (uint64_t)desc->block_size * desc->n_kv_heads * desc->head_dim * desc->elem_bytes;
+    if (F % 16 != 0 || F > (1ull << 34)) return MP_EINVAL;
+    if (((uintptr_t)desc->base & 15u) || ((uintptr_t)desc->staging & 15u)) return MP_EINVAL;
+    mp_pool *p = new mp_pool;
+    p->desc = *desc;
+    p->F = F;
+    p->P = 2 * desc->n_layers;
+    p->B = F * p->P;
+    p->idx.init(desc->n_blocks, desc->block_size, desc->tier, desc->instance_id);
+    *out = p;
+    return MP_OK;
+  }
+  MP_CATCH(nullptr)
 }
 
 int mp_pool_destroy(mp_pool_t *p) {
@@ -791,12 +841,7 @@ int mp_pool_destroy(mp_pool_t *p) {
     mirror_disable(p);
     release(d.m_updates);
     release(d.m_out);
-    for (int s = 0; s < DeviceCtx::kTableSlots; ++s) (void)hipEventDestroy(d.tables_uploaded[s]);
-    for (int s = 0; s < 2; ++s) {
-      (void)hipEventDestroy(d.slot_filled[s]);
-      (void)hipEventDestroy(d.slot_drained[s]);
-    }
-    (void)hipStreamDestroy(d.side);
+    destroy_device_objects(d);
   }
   delete p;
   return MP_OK;
@@ -816,308 +861,365 @@ int mp_pool_stats(mp_pool_t *p, mp_pool_stats_t *out) {
 const char *mp_last_error(mp_pool_t *p) { return p ? p->err.c_str() : "null pool"; }
 
 int mp_alloc(mp_pool_t *p, uint32_t n, int32_t *blocks_out, uint32_t flags) {
-  if (!p) return MP_EINVAL;
-  if (!blocks_out && n) return fail(p, MP_EINVAL, "null output array");
-  if (!p->idx.alloc(n, blocks_out, (flags & MP_EVICT_ON_DEMAND) != 0))
-    return fail(p, MP_ENOMEM, "not enough free (or evictable) blocks");
-  return MP_OK;
+  try {
+    if (!p) return MP_EINVAL;
+    if (!blocks_out && n) return fail(p, MP_EINVAL, "null output array");
+    if (!p->idx.alloc(n, blocks_out, (flags & MP_EVICT_ON_DEMAND) != 0))
+      return fail(p, MP_ENOMEM, "not enough free (or evictable) blocks");
+    return MP_OK;
+  }
+  MP_CATCH(p)
 }
 
 int mp_free(mp_pool_t *p, const int32_t *blocks, uint32_t n) {
-  if (!p) return MP_EINVAL;
-  if (!blocks && n) return fail(p, MP_EINVAL, "null block list");
-  if (!p->idx.release(blocks, n)) return fail(p, MP_EINVAL, "id out of range or not referenced");
-  return MP_OK;
+  try {
+    if (!p) return MP_EINVAL;
+    if (!blocks && n) return fail(p, MP_EINVAL, "null block list");
+    if (!p->idx.release(blocks, n)) return fail(p, MP_EINVAL, "id out of range or not referenced");
+    return MP_OK;
+  }
+  MP_CATCH(p)
 }
 
 int mp_insert_hashed(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens,
                      const uint64_t *hashes, const int32_t *blocks, uint32_t n_blocks,
                      uint32_t flags, uint32_t *n_new_out) {
-  (void)flags;
-  if (!p) return MP_EINVAL;
-  if ((!tokens && n_tokens) || !n_new_out) return fail(p, MP_EINVAL, "null argument");
-  const uint32_t nb = n_tokens / p->desc.block_size;
-  if (n_blocks < nb || ((!blocks || !hashes) && nb))
-    return fail(p, MP_EINVAL, "fewer block ids than full blocks");
-  const uint32_t m = p->idx.walk(tokens, hashes, nb, nullptr);
-  if (!p->idx.adoptable(blocks, m, nb))
-    return fail(p, MP_EINVAL, "blocks to adopt must be held, un-indexed and distinct");
-  *n_new_out = p->idx.insert(tokens, hashes, nb, blocks);
-  return MP_OK;
+  try {
+    (void)flags;
+    if (!p) return MP_EINVAL;
+    if ((!tokens && n_tokens) || !n_new_out) return fail(p, MP_EINVAL, "null argument");
+    const uint32_t nb = n_tokens / p->desc.block_size;
+    if (n_blocks < nb || ((!blocks || !hashes) && nb))
+      return fail(p, MP_EINVAL, "fewer block ids than full blocks");
+    const uint32_t m = p->idx.walk(tokens, hashes, nb, nullptr);
+    if (!p->idx.adoptable(blocks, m, nb))
+      return fail(p, MP_EINVAL, "blocks to adopt must be held, un-indexed and distinct");
+    *n_new_out = p->idx.insert(tokens, hashes, nb, blocks);
+    return MP_OK;
+  }
+  MP_CATCH(p)
 }
 
 int mp_match_hashed(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens,
                     const uint64_t *hashes, int32_t *blocks_out, uint32_t cap,
                     uint32_t *n_matched_out, uint32_t flags) {
-  if (!p) return MP_EINVAL;
-  if ((!tokens && n_tokens) || !n_matched_out || (!blocks_out && cap))
-    return fail(p, MP_EINVAL, "null argument");
-  uint32_t nb = std::min(n_tokens / p->desc.block_size, cap);
-  if (!hashes && nb) return fail(p, MP_EINVAL, "null hashes");
-  match_walk(p, tokens, hashes, nb, blocks_out, n_matched_out, flags);
-  return MP_OK;
+  try {
+    if (!p) return MP_EINVAL;
+    if ((!tokens && n_tokens) || !n_matched_out || (!blocks_out && cap))
+      return fail(p, MP_EINVAL, "null argument");
+    uint32_t nb = std::min(n_tokens / p->desc.block_size, cap);
+    if (!hashes && nb) return fail(p, MP_EINVAL, "null hashes");
+    match_walk(p, tokens, hashes, nb, blocks_out, n_matched_out, flags);
+    return MP_OK;
+  }
+  MP_CATCH(p)
 }
 
 int mp_block_hashes(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, uint64_t *out,
                     uint32_t flags) {
-  if (!p) return MP_EINVAL;
-  if ((!tokens && n_tokens) || (!out && n_tokens / p->desc.block_size))
-    return fail(p, MP_EINVAL, "null argument");
-  const uint32_t tok_off[2] = {0, n_tokens};
-  std::vector<uint32_t> hoff;
-  const uint32_t *htok;
-  const uint64_t *hh;
-  int rc = device_hashes(p, tokens, tok_off, 1, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok, &hh);
-  if (rc != MP_OK) return rc;
-  std::memcpy(out, hh, 8ull * hoff[1]);
-  return MP_OK;
+  try {
+    if (!p) return MP_EINVAL;
+    if ((!tokens && n_tokens) || (!out && n_tokens / p->desc.block_size))
+      return fail(p, MP_EINVAL, "null argument");
+    const uint32_t tok_off[2] = {0, n_tokens};
+    std::vector<uint32_t> hoff;
+    const uint32_t *htok;
+    const uint64_t *hh;
+    int rc = device_hashes(p, tokens, tok_off, 1, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok, &hh);
+    if (rc != MP_OK) return rc;
+    std::memcpy(out, hh, 8ull * hoff[1]);
+    return MP_OK;
+  }
+  MP_CATCH(p)
 }
 
 int mp_block_hashes_batch(mp_pool_t *p, const uint32_t *tokens, const uint32_t *tok_off,
                           uint32_t n_req, uint64_t *out, uint32_t flags) {
-  if (!p) return MP_EINVAL;
-  if (!tok_off) return fail(p, MP_EINVAL, "null argument");
-  if (tok_off[0] != 0) return fail(p, MP_EINVAL, "offsets must start at 0");
-  for (uint32_t r = 0; r < n_req; ++r)
-    if (tok_off[r + 1] < tok_off[r]) return fail(p, MP_EINVAL, "offsets must be non-decreasing");
-  if (!tokens && tok_off[n_req]) return fail(p, MP_EINVAL, "null tokens");
-  std::vector<uint32_t> hoff;
-  const uint32_t *htok;
-  const uint64_t *hh;
-  int rc = device_hashes(p, tokens, tok_off, n_req, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok,
-                         &hh);
-  if (rc != MP_OK) return rc;
-  if (hoff[n_req] && !out) return fail(p, MP_EINVAL, "null output array");
-  std::memcpy(out, hh, 8ull * hoff[n_req]);
-  return MP_OK;
+  try {
+    if (!p) return MP_EINVAL;
+    if (!tok_off) return fail(p, MP_EINVAL, "null argument");
+    if (tok_off[0] != 0) return fail(p, MP_EINVAL, "offsets must start at 0");
+    for (uint32_t r = 0; r < n_req; ++r)
+      if (tok_off[r + 1] < tok_off[r]) return fail(p, MP_EINVAL, "offsets must be non-decreasing");
+    if (!tokens && tok_off[n_req]) return fail(p, MP_EINVAL, "null tokens");
+    std::vector<uint32_t> hoff;
+    const uint32_t *htok;
+    const uint64_t *hh;
+    int rc = device_hashes(p, tokens, tok_off, n_req, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok,
+                           &hh);
+    if (rc != MP_OK) return rc;
+    if (hoff[n_req] && !out) return fail(p, MP_EINVAL, "null output array");
+    std::memcpy(out, hh, 8ull * hoff[n_req]);
+    return MP_OK;
+  }
+  MP_CATCH(p)
 }
 
 int mp_insert(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, const int32_t *blocks,
               uint32_t n_blocks, uint32_t flags, uint32_t *n_new_out) {
-  if (!p) return MP_EINVAL;
-  if ((!tokens && n_tokens) || !n_new_out) return fail(p, MP_EINVAL, "null argument");
-  const uint32_t nb = n_tokens / p->desc.block_size;
-  if (n_blocks < nb || (!blocks && nb)) return fail(p, MP_EINVAL, "fewer block ids than full blocks");
-  const uint32_t tok_off[2] = {0, n_tokens};
-  std::vector<uint32_t> hoff;
-  const uint32_t *htok;
-  const uint64_t *hh;
-  int rc = device_hashes(p, tokens, tok_off, 1, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok, &hh);
-  if (rc != MP_OK) return rc;
-  return mp_insert_hashed(p, htok, n_tokens, hh, blocks, n_blocks, flags, n_new_out);
+  try {
+    if (!p) return MP_EINVAL;
+    if ((!tokens && n_tokens) || !n_new_out) return fail(p, MP_EINVAL, "null argument");
+    const uint32_t nb = n_tokens / p->desc.block_size;
+    if (n_blocks < nb || (!blocks && nb)) return fail(p, MP_EINVAL, "fewer block ids than full blocks");
+    const uint32_t tok_off[2] = {0, n_tokens};
+    std::vector<uint32_t> hoff;
+    const uint32_t *htok;
+    const uint64_t *hh;
+    int rc = device_hashes(p, tokens, tok_off, 1, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok, &hh);
+    if (rc != MP_OK) return rc;
+    return mp_insert_hashed(p, htok, n_tokens, hh, blocks, n_blocks, flags, n_new_out);
+  }
+  MP_CATCH(p)
 }
 
 int mp_match_batch(mp_pool_t *p, const uint32_t *tokens, const uint32_t *tok_off, uint32_t n_req,
                    int32_t *blocks_out, const uint32_t *blk_off, uint32_t *n_matched_out,
                    uint32_t flags) {
-  if (!p) return MP_EINVAL;
-  if (!tok_off || !blk_off || (!n_matched_out && n_req)) return fail(p, MP_EINVAL, "null argument");
-  if (tok_off[0] != 0) return fail(p, MP_EINVAL, "offsets must start at 0");
-  for (uint32_t r = 0; r < n_req; ++r)
-    if (tok_off[r + 1] < tok_off[r] || blk_off[r + 1] < blk_off[r])
-      return fail(p, MP_EINVAL, "offsets must be non-decreasing");
-  if (!tokens && tok_off[n_req]) return fail(p, MP_EINVAL, "null tokens");
-  if (!blocks_out && blk_off[n_req] != blk_off[0]) return fail(p, MP_EINVAL, "null output array");
-  std::vector<uint32_t> hoff;
-  const uint32_t *htok;
-  const uint64_t *hh;
-  if (p->dev.mirror_on && n_req) {
-    // device probe: slot offsets relative to the first request's slot; the host only stamps,
-    // pins and copies out what the kernel found
-    std::vector<uint32_t> rel(n_req + 1);
-    for (uint32_t r = 0; r <= n_req; ++r) rel[r] = blk_off[r] - blk_off[0];
-    int rc = device_hashes(p, tokens, tok_off, n_req, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff,
-                           &htok, &hh, rel.data());
+  try {
+    if (!p) return MP_EINVAL;
+    if (!tok_off || !blk_off || (!n_matched_out && n_req)) return fail(p, MP_EINVAL, "null argument");
+    if (tok_off[0] != 0) return fail(p, MP_EINVAL, "offsets must start at 0");
+    for (uint32_t r = 0; r < n_req; ++r)
+      if (tok_off[r + 1] < tok_off[r] || blk_off[r + 1] < blk_off[r])
+        return fail(p, MP_EINVAL, "offsets must be non-decreasing");
+    if (!tokens && tok_off[n_req]) return fail(p, MP_EINVAL, "null tokens");
+    if (!blocks_out && blk_off[n_req] != blk_off[0]) return fail(p, MP_EINVAL, "null output array");
+    std::vector<uint32_t> hoff;
+    const uint32_t *htok;
+    const uint64_t *hh;
+    if (p->dev.mirror_on && n_req) {
+      // device probe: slot offsets relative to the first request's slot; the host only stamps,
+      // pins and copies out what the kernel found
+      std::vector<uint32_t> rel(n_req + 1);
+      for (uint32_t r = 0; r <= n_req; ++r) rel[r] = blk_off[r] - blk_off[0];
+      int rc = device_hashes(p, tokens, tok_off, n_req, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff,
+                             &htok, &hh, rel.data());
+      if (rc != MP_OK) return rc;
+      const uint32_t *o = (const uint32_t *)p->dev.m_out.host;
+      const uint32_t *cnt = o + n_req + 1;
+      const int32_t *ids = (const int32_t *)(o + 2ull * n_req + 1);
+      for (uint32_t r = 0; r < n_req; ++r) {
+        p->idx.tick();
+        const bool any = hoff[r + 1] > hoff[r] && rel[r + 1] > rel[r];
+        const uint32_t m = any ? cnt[r] : 0;
+        int32_t *dst = blocks_out + blk_off[r];
+        if (m) std::memcpy(dst, ids + rel[r], 4ull * m);
+        p->idx.touch(dst, m);
+        if (flags & MP_MATCH_PIN)
+          for (uint32_t i = 0; i < m; ++i) p->idx.pin(dst[i]);
+        n_matched_out[r] = m;
+      }
+      return MP_OK;
+    }
+    int rc = device_hashes(p, tokens, tok_off, n_req, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok,
+                           &hh);
     if (rc != MP_OK) return rc;
-    const uint32_t *o = (const uint32_t *)p->dev.m_out.host;
-    const uint32_t *cnt = o + n_req + 1;
-    const int32_t *ids = (const int32_t *)(o + 2ull * n_req + 1);
     for (uint32_t r = 0; r < n_req; ++r) {
-      p->idx.tick();
-      const bool any = hoff[r + 1] > hoff[r] && rel[r + 1] > rel[r];
-      const uint32_t m = any ? cnt[r] : 0;
-      int32_t *dst = blocks_out + blk_off[r];
-      if (m) std::memcpy(dst, ids + rel[r], 4ull * m);
-      p->idx.touch(dst, m);
-      if (flags & MP_MATCH_PIN)
-        for (uint32_t i = 0; i < m; ++i) p->idx.pin(dst[i]);
-      n_matched_out[r] = m;
+      const uint32_t nb = std::min(hoff[r + 1] - hoff[r], blk_off[r + 1] - blk_off[r]);
+      match_walk(p, htok + tok_off[r], hh + hoff[r], nb, blocks_out + blk_off[r], &n_matched_out[r],
+                 flags);
     }
     return MP_OK;
   }
-  int rc = device_hashes(p, tokens, tok_off, n_req, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok,
-                         &hh);
-  if (rc != MP_OK) return rc;
-  for (uint32_t r = 0; r < n_req; ++r) {
-    const uint32_t nb = std::min(hoff[r + 1] - hoff[r], blk_off[r + 1] - blk_off[r]);
-    match_walk(p, htok + tok_off[r], hh + hoff[r], nb, blocks_out + blk_off[r], &n_matched_out[r],
-               flags);
-  }
-  return MP_OK;
+  MP_CATCH(p)
 }
 
 int mp_match(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, int32_t *blocks_out,
              uint32_t cap, uint32_t *n_matched_out, uint32_t flags) {
-  if (!p) return MP_EINVAL;
-  if (!n_matched_out) return fail(p, MP_EINVAL, "null argument");
-  const uint32_t tok_off[2] = {0, n_tokens}, blk_off[2] = {0, cap};
-  return mp_match_batch(p, tokens, tok_off, 1, blocks_out, blk_off, n_matched_out, flags);
+  try {
+    if (!p) return MP_EINVAL;
+    if (!n_matched_out) return fail(p, MP_EINVAL, "null argument");
+    const uint32_t tok_off[2] = {0, n_tokens}, blk_off[2] = {0, cap};
+    return mp_match_batch(p, tokens, tok_off, 1, blocks_out, blk_off, n_matched_out, flags);
+  }
+  MP_CATCH(p)
 }
 
 int mp_delete_hashed(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens,
                      const uint64_t *hashes, uint32_t *n_deleted_out) {
-  if (!p) return MP_EINVAL;
-  if ((!tokens && n_tokens) || !n_deleted_out) return fail(p, MP_EINVAL, "null argument");
-  const uint32_t nb = n_tokens / p->desc.block_size;
-  if (!hashes && nb) return fail(p, MP_EINVAL, "null hashes");
-  std::vector<int32_t> &path = p->scratch_ids;
-  path.resize(nb);
-  const uint32_t m = p->idx.walk(tokens, hashes, nb, path.data());
-  *n_deleted_out = p->idx.erase_path(path.data(), m);
-  return MP_OK;
+  try {
+    if (!p) return MP_EINVAL;
+    if ((!tokens && n_tokens) || !n_deleted_out) return fail(p, MP_EINVAL, "null argument");
+    const uint32_t nb = n_tokens / p->desc.block_size;
+    if (!hashes && nb) return fail(p, MP_EINVAL, "null hashes");
+    std::vector<int32_t> &path = p->scratch_ids;
+    path.resize(nb);
+    const uint32_t m = p->idx.walk(tokens, hashes, nb, path.data());
+    *n_deleted_out = p->idx.erase_path(path.data(), m);
+    return MP_OK;
+  }
+  MP_CATCH(p)
 }
 
 int mp_delete(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, uint32_t flags,
               uint32_t *n_deleted_out) {
-  if (!p) return MP_EINVAL;
-  if ((!tokens && n_tokens) || !n_deleted_out) return fail(p, MP_EINVAL, "null argument");
-  const uint32_t tok_off[2] = {0, n_tokens};
-  std::vector<uint32_t> hoff;
-  const uint32_t *htok;
-  const uint64_t *hh;
-  int rc = device_hashes(p, tokens, tok_off, 1, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok, &hh);
-  if (rc != MP_OK) return rc;
-  return mp_delete_hashed(p, htok, n_tokens, hh, n_deleted_out);
+  try {
+    if (!p) return MP_EINVAL;
+    if ((!tokens && n_tokens) || !n_deleted_out) return fail(p, MP_EINVAL, "null argument");
+    const uint32_t tok_off[2] = {0, n_tokens};
+    std::vector<uint32_t> hoff;
+    const uint32_t *htok;
+    const uint64_t *hh;
+    int rc = device_hashes(p, tokens, tok_off, 1, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok, &hh);
+    if (rc != MP_OK) return rc;
+    return mp_delete_hashed(p, htok, n_tokens, hh, n_deleted_out);
+  }
+  MP_CATCH(p)
 }
 
 int mp_evict(mp_pool_t *p, uint32_t n_blocks, uint32_t *n_evicted_out) {
-  if (!p) return MP_EINVAL;
-  if (!n_evicted_out) return fail(p, MP_EINVAL, "null argument");
-  *n_evicted_out = p->idx.evict(n_blocks);
-  return MP_OK;
+  try {
+    if (!p) return MP_EINVAL;
+    if (!n_evicted_out) return fail(p, MP_EINVAL, "null argument");
+    *n_evicted_out = p->idx.evict(n_blocks);
+    return MP_OK;
+  }
+  MP_CATCH(p)
 }
 
 int mp_transfer(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks, int32_t *dst_blocks,
                 uint32_t n, uint32_t flags, const void *priv, uint64_t priv_len) {
-  if (!src || !dst) return MP_EINVAL;
-  if ((!src_blocks || !dst_blocks) && n) return fail(src, MP_EINVAL, "null block table");
-  if (!same_geometry(src, dst)) return fail(src, MP_ESHAPE, "source and destination geometry differ");
-  int rc = check_src_ids(src, src_blocks, n);
-  if (rc != MP_OK) return rc;
-  if ((flags & MP_DST_GIVEN) && !dst->idx.held_and_distinct(dst_blocks, n))
-    return fail(src, MP_EINVAL, "given destination ids must be held and distinct");
-  if ((rc = check_copy_feasible(src, dst, n, flags)) != MP_OK) return rc;
-  if ((rc = check_same_pool(src, dst, src_blocks, dst_blocks, n, flags)) != MP_OK) return rc;
-  if (!(flags & MP_DST_GIVEN) &&
-      !dst->idx.alloc(n, dst_blocks, (flags & MP_EVICT_ON_DEMAND) != 0))
-    return fail(src, MP_ENOMEM, "destination pool cannot supply the blocks");
-  rc = run_copy(src, dst, src_blocks, dst_blocks, n, flags);
-  if (rc == MP_OK) rc = finish_copy(src, dst, flags);
-  if (rc != MP_OK) return rc;
-  if (dst->cb) dst->cb(dst->cb_user, priv, priv_len, dst_blocks, n);
-  return MP_OK;
+  try {
+    if (!src || !dst) return MP_EINVAL;
+    if ((!src_blocks || !dst_blocks) && n) return fail(src, MP_EINVAL, "null block table");
+    if (!same_geometry(src, dst)) return fail(src, MP_ESHAPE, "source and destination geometry differ");
+    int rc = check_src_ids(src, src_blocks, n);
+    if (rc != MP_OK) return rc;
+    if ((flags & MP_DST_GIVEN) && !dst->idx.held_and_distinct(dst_blocks, n))
+      return fail(src, MP_EINVAL, "given destination ids must be held and distinct");
+    if ((rc = check_copy_feasible(src, dst, n, flags)) != MP_OK) return rc;
+    if ((rc = check_same_pool(src, dst, src_blocks, dst_blocks, n, flags)) != MP_OK) return rc;
+    if (!(flags & MP_DST_GIVEN) &&
+        !dst->idx.alloc(n, dst_blocks, (flags & MP_EVICT_ON_DEMAND) != 0))
+      return fail(src, MP_ENOMEM, "destination pool cannot supply the blocks");
+    rc = run_copy(src, dst, src_blocks, dst_blocks, n, flags);
+    if (rc == MP_OK) rc = finish_copy(src, dst, flags);
+    if (rc != MP_OK) return rc;
+    if (dst->cb) dst->cb(dst->cb_user, priv, priv_len, dst_blocks, n);
+    return MP_OK;
+  }
+  MP_CATCH(src)
 }
 
 int mp_transfer_batch(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks,
                       int32_t *dst_blocks, const uint32_t *blk_off, uint32_t n_req,
                       uint32_t flags) {
-  if (!src || !dst) return MP_EINVAL;
-  if (!blk_off) return fail(src, MP_EINVAL, "null offsets");
-  if (blk_off[0] != 0) return fail(src, MP_EINVAL, "offsets must start at 0");
-  for (uint32_t r = 0; r < n_req; ++r)
-    if (blk_off[r + 1] < blk_off[r]) return fail(src, MP_EINVAL, "offsets must be non-decreasing");
-  return mp_transfer(src, dst, src_blocks, dst_blocks, blk_off[n_req], flags, nullptr, 0);
+  try {
+    if (!src || !dst) return MP_EINVAL;
+    if (!blk_off) return fail(src, MP_EINVAL, "null offsets");
+    if (blk_off[0] != 0) return fail(src, MP_EINVAL, "offsets must start at 0");
+    for (uint32_t r = 0; r < n_req; ++r)
+      if (blk_off[r + 1] < blk_off[r]) return fail(src, MP_EINVAL, "offsets must be non-decreasing");
+    return mp_transfer(src, dst, src_blocks, dst_blocks, blk_off[n_req], flags, nullptr, 0);
+  }
+  MP_CATCH(src)
 }
 
 int mp_transfer_layers(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks,
                        const int32_t *dst_blocks, uint32_t n, uint32_t layer_begin,
                        uint32_t layer_end, uint32_t flags) {
-  if (!src || !dst) return MP_EINVAL;
-  if ((!src_blocks || !dst_blocks) && n) return fail(src, MP_EINVAL, "null block table");
-  if (!same_geometry(src, dst)) return fail(src, MP_ESHAPE, "source and destination geometry differ");
-  if (layer_begin >= layer_end || layer_end > src->desc.n_layers)
-    return fail(src, MP_EINVAL, "layer range must be non-empty and inside [0, n_layers]");
-  int rc = check_src_ids(src, src_blocks, n);
-  if (rc != MP_OK) return rc;
-  if (!dst->idx.held_and_distinct(dst_blocks, n))
-    return fail(src, MP_EINVAL, "destination ids must be held and distinct");
-  if ((rc = check_copy_feasible(src, dst, n, flags, layer_end - layer_begin)) != MP_OK) return rc;
-  if (src == dst && n && tables_overlap(src, src_blocks, dst_blocks, n)) {
-    if (flags & MP_DIRECT)
-      return fail(src, MP_EINVAL, "MP_DIRECT within one pool needs disjoint tables");
-    if ((uint64_t)n * 2ull * (layer_end - layer_begin) * src->F > src->desc.staging_bytes)
-      return fail(src, MP_ENOSTAGING, "overlapping in-pool transfer must fit the staging buffer");
+  try {
+    if (!src || !dst) return MP_EINVAL;
+    if ((!src_blocks || !dst_blocks) && n) return fail(src, MP_EINVAL, "null block table");
+    if (!same_geometry(src, dst)) return fail(src, MP_ESHAPE, "source and destination geometry differ");
+    if (layer_begin >= layer_end || layer_end > src->desc.n_layers)
+      return fail(src, MP_EINVAL, "layer range must be non-empty and inside [0, n_layers]");
+    int rc = check_src_ids(src, src_blocks, n);
+    if (rc != MP_OK) return rc;
+    if (!dst->idx.held_and_distinct(dst_blocks, n))
+      return fail(src, MP_EINVAL, "destination ids must be held and distinct");
+    if ((rc = check_copy_feasible(src, dst, n, flags, layer_end - layer_begin)) != MP_OK) return rc;
+    if (src == dst && n && tables_overlap(src, src_blocks, dst_blocks, n)) {
+      if (flags & MP_DIRECT)
+        return fail(src, MP_EINVAL, "MP_DIRECT within one pool needs disjoint tables");
+      if ((uint64_t)n * 2ull * (layer_end - layer_begin) * src->F > src->desc.staging_bytes)
+        return fail(src, MP_ENOSTAGING, "overlapping in-pool transfer must fit the staging buffer");
+    }
+    rc = run_copy(src, dst, src_blocks, dst_blocks, n, flags, layer_begin, layer_end);
+    if (rc == MP_OK) rc = finish_copy(src, dst, flags);
+    return rc;
   }
-  rc = run_copy(src, dst, src_blocks, dst_blocks, n, flags, layer_begin, layer_end);
-  if (rc == MP_OK) rc = finish_copy(src, dst, flags);
-  return rc;
+  MP_CATCH(src)
 }
 
 int mp_transfer_with_insert(mp_pool_t *src, mp_pool_t *dst, const uint32_t *tokens,
                             uint32_t n_tokens, uint32_t first_block, const int32_t *src_blocks,
                             int32_t *dst_blocks, uint32_t n, uint32_t flags, const void *priv,
                             uint64_t priv_len) {
-  const uint32_t tok_off[2] = {0, n_tokens}, blk_off[2] = {0, n};
-  return twi_core(src, dst, tokens, tok_off, 1, &first_block, src_blocks, dst_blocks, blk_off,
-                  flags, priv, priv_len);
+  try {
+    const uint32_t tok_off[2] = {0, n_tokens}, blk_off[2] = {0, n};
+    return twi_core(src, dst, tokens, tok_off, 1, &first_block, src_blocks, dst_blocks, blk_off,
+                    flags, priv, priv_len);
+  }
+  MP_CATCH(src)
 }
 
 int mp_transfer_with_insert_batch(mp_pool_t *src, mp_pool_t *dst, const uint32_t *tokens,
                                   const uint32_t *tok_off, uint32_t n_req,
                                   const uint32_t *first_block, const int32_t *src_blocks,
                                   int32_t *dst_blocks, const uint32_t *blk_off, uint32_t flags) {
-  if (src && (flags & MP_DST_GIVEN))
-    return fail(src, MP_EINVAL, "MP_DST_GIVEN is not supported in batched form");
-  return twi_core(src, dst, tokens, tok_off, n_req, first_block, src_blocks, dst_blocks, blk_off,
-                  flags, nullptr, 0);
+  try {
+    if (src && (flags & MP_DST_GIVEN))
+      return fail(src, MP_EINVAL, "MP_DST_GIVEN is not supported in batched form");
+    return twi_core(src, dst, tokens, tok_off, n_req, first_block, src_blocks, dst_blocks, blk_off,
+                    flags, nullptr, 0);
+  }
+  MP_CATCH(src)
 }
 
 int mp_gather(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags) {
-  if (!p) return MP_EINVAL;
-  if (!tbl && n) return fail(p, MP_EINVAL, "null table");
-  if (p->desc.tier != MP_TIER_HBM) return fail(p, MP_EINVAL, "mp_gather needs an HBM pool");
-  for (uint32_t i = 0; i < n; ++i)
-    if (!p->idx.in_range(tbl[i])) return fail(p, MP_EINVAL, "block id out of range");
-  if (n == 0) return MP_OK;
-  if (!p->desc.staging || (uint64_t)n * p->B > p->desc.staging_bytes)
-    return fail(p, MP_ENOSTAGING, "staging buffer too small for the table");
-  int rc = ensure_device(p);
-  if (rc != MP_OK) return rc;
-  const int32_t *d_src, *d_dst;
-  if ((rc = upload_tables(p, tbl, nullptr, n, &d_src, &d_dst)) != MP_OK) return rc;
-  {
-    ProfScope ps(p, kProfGather, 2ull * n * p->B);
-    HIP_TRY(p, launch_block_copy(pool_side(p, d_src), record_side(p, p->desc.staging, p->P), n, p->P,
-                                 p->F, p->tune, p->dev.n_cus, p->dev.stream));
+  try {
+    if (!p) return MP_EINVAL;
+    if (!tbl && n) return fail(p, MP_EINVAL, "null table");
+    if (p->desc.tier != MP_TIER_HBM) return fail(p, MP_EINVAL, "mp_gather needs an HBM pool");
+    for (uint32_t i = 0; i < n; ++i)
+      if (!p->idx.in_range(tbl[i])) return fail(p, MP_EINVAL, "block id out of range");
+    if (n == 0) return MP_OK;
+    if (!p->desc.staging || (uint64_t)n * p->B > p->desc.staging_bytes)
+      return fail(p, MP_ENOSTAGING, "staging buffer too small for the table");
+    int rc = ensure_device(p);
+    if (rc != MP_OK) return rc;
+    const int32_t *d_src, *d_dst;
+    if ((rc = upload_tables(p, tbl, nullptr, n, &d_src, &d_dst)) != MP_OK) return rc;
+    {
+      ProfScope ps(p, kProfGather, 2ull * n * p->B);
+      HIP_TRY(p, launch_block_copy(pool_side(p, d_src), record_side(p, p->desc.staging, p->P), n, p->P,
+                                   p->F, p->tune, p->dev.n_cus, p->dev.stream));
+    }
+    if (!(flags & MP_ASYNC)) HIP_TRY(p, hipStreamSynchronize(p->dev.stream));
+    return MP_OK;
   }
-  if (!(flags & MP_ASYNC)) HIP_TRY(p, hipStreamSynchronize(p->dev.stream));
-  return MP_OK;
+  MP_CATCH(p)
 }
 
 int mp_scatter(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags) {
-  if (!p) return MP_EINVAL;
-  if (!tbl && n) return fail(p, MP_EINVAL, "null table");
-  if (p->desc.tier != MP_TIER_HBM) return fail(p, MP_EINVAL, "mp_scatter needs an HBM pool");
-  std::vector<uint8_t> seen(p->desc.n_blocks, 0);
-  for (uint32_t i = 0; i < n; ++i) {
-    if (!p->idx.in_range(tbl[i]) || seen[tbl[i]])
-      return fail(p, MP_EINVAL, "block id out of range or repeated");
-    seen[tbl[i]] = 1;
+  try {
+    if (!p) return MP_EINVAL;
+    if (!tbl && n) return fail(p, MP_EINVAL, "null table");
+    if (p->desc.tier != MP_TIER_HBM) return fail(p, MP_EINVAL, "mp_scatter needs an HBM pool");
+    std::vector<uint8_t> seen(p->desc.n_blocks, 0);
+    for (uint32_t i = 0; i < n; ++i) {
+      if (!p->idx.in_range(tbl[i]) || seen[tbl[i]])
+        return fail(p, MP_EINVAL, "block id out of range or repeated");
+      seen[tbl[i]] = 1;
+    }
+    if (n == 0) return MP_OK;
+    if (!p->desc.staging || (uint64_t)n * p->B > p->desc.staging_bytes)
+      return fail(p, MP_ENOSTAGING, "staging buffer too small for the table");
+    int rc = ensure_device(p);
+    if (rc != MP_OK) return rc;
+    const int32_t *d_src, *d_dst;
+    if ((rc = upload_tables(p, nullptr, tbl, n, &d_src, &d_dst)) != MP_OK) return rc;
+    {
+      ProfScope ps(p, kProfScatter, 2ull * n * p->B);
+      HIP_TRY(p, launch_block_copy(record_side(p, p->desc.staging, p->P), pool_side(p, d_dst), n, p->P,
+                                   p->F, p->tune, p->dev.n_cus, p->dev.stream));
+    }
+    if (!(flags & MP_ASYNC)) HIP_TRY(p, hipStreamSynchronize(p->dev.stream));
+    return MP_OK;
   }
-  if (n == 0) return MP_OK;
-  if (!p->desc.staging || (uint64_t)n * p->B > p->desc.staging_bytes)
-    return fail(p, MP_ENOSTAGING, "staging buffer too small for the table");
-  int rc = ensure_device(p);
-  if (rc != MP_OK) return rc;
-  const int32_t *d_src, *d_dst;
-  if ((rc = upload_tables(p, nullptr, tbl, n, &d_src, &d_dst)) != MP_OK) return rc;
-  {
-    ProfScope ps(p, kProfScatter, 2ull * n * p->B);
-    HIP_TRY(p, launch_block_copy(record_side(p, p->desc.staging, p->P), pool_side(p, d_dst), n, p->P,
-                                 p->F, p->tune, p->dev.n_cus, p->dev.stream));
-  }
-  if (!(flags & MP_ASYNC)) HIP_TRY(p, hipStreamSynchronize(p->dev.stream));
-  return MP_OK;
+  MP_CATCH(p)
 }
 
 int mp_set_recv_callback(mp_pool_t *p, mp_recv_cb cb, void *user) {
@@ -1135,16 +1237,19 @@ int mp_profile_enable(mp_pool_t *p, int on) {
 
 int mp_profile_read(mp_pool_t *p, int kind, double *total_ms_out, uint64_t *launches_out,
                     uint64_t *bytes_out) {
-  if (!p) return MP_EINVAL;
-  if (kind < 0 || kind >= kProfKinds) return fail(p, MP_EINVAL, "unknown kernel kind");
-  prof_drain(p);
-  if (total_ms_out) *total_ms_out = p->dev.prof_ms[kind];
-  if (launches_out) *launches_out = p->dev.prof_launches[kind];
-  if (bytes_out) *bytes_out = p->dev.prof_bytes[kind];
-  p->dev.prof_ms[kind] = 0;
-  p->dev.prof_launches[kind] = 0;
-  p->dev.prof_bytes[kind] = 0;
-  return MP_OK;
+  try {
+    if (!p) return MP_EINVAL;
+    if (kind < 0 || kind >= kProfKinds) return fail(p, MP_EINVAL, "unknown kernel kind");
+    prof_drain(p);
+    if (total_ms_out) *total_ms_out = p->dev.prof_ms[kind];
+    if (launches_out) *launches_out = p->dev.prof_launches[kind];
+    if (bytes_out) *bytes_out = p->dev.prof_bytes[kind];
+    p->dev.prof_ms[kind] = 0;
+    p->dev.prof_launches[kind] = 0;
+    p->dev.prof_bytes[kind] = 0;
+    return MP_OK;
+  }
+  MP_CATCH(p)
 }
 
 int mp_plain_copy(void *dst, const void *src, uint64_t bytes, void *stream, double *ms_out) {
@@ -1169,22 +1274,25 @@ int mp_plain_copy(void *dst, const void *src, uint64_t bytes, void *stream, doub
 }
 
 int mp_set_tunable(mp_pool_t *p, const char *key, int value) {
-  if (!p || !key) return MP_EINVAL;
-  const std::string k(key);
-  const bool dflt = value == -1;  // -1 restores the geometry-based default
-  if (k == "order" && (dflt || value == 0 || value == 1)) p->tune.order = value;
-  else if (k == "unroll" && (dflt || value == 1 || value == 2 || value == 4 || value == 8)) p->tune.unroll = value;
-  else if (k == "wg_per_cu" && value >= -1 && value <= 64) p->tune.wg_per_cu = value;
-  else if (k == "nontemporal" && (dflt || value == 0 || value == 1)) p->tune.nontemporal = value;
-  else if (k == "waves_per_wg" && (dflt || value == 1 || value == 4)) p->tune.waves_per_wg = value;
-  else if (k == "xcd_contiguous" && (dflt || value == 0 || value == 1)) p->tune.xcd_contiguous = value;
-  else if (k == "item_limit" && value >= 0) p->tune.item_limit = value;
-  else if (k == "device_probe" && (value == 0 || value == 1)) {
-    if (value) return mirror_enable(p);
-    mirror_disable(p);
+  try {
+    if (!p || !key) return MP_EINVAL;
+    const std::string k(key);
+    const bool dflt = value == -1;  // -1 restores the geometry-based default
+    if (k == "order" && (dflt || value == 0 || value == 1)) p->tune.order = value;
+    else if (k == "unroll" && (dflt || value == 1 || value == 2 || value == 4 || value == 8)) p->tune.unroll = value;
+    else if (k == "wg_per_cu" && value >= -1 && value <= 64) p->tune.wg_per_cu = value;
+    else if (k == "nontemporal" && (dflt || value == 0 || value == 1)) p->tune.nontemporal = value;
+    else if (k == "waves_per_wg" && (dflt || value == 1 || value == 4)) p->tune.waves_per_wg = value;
+    else if (k == "xcd_contiguous" && (dflt || value == 0 || value == 1)) p->tune.xcd_contiguous = value;
+    else if (k == "item_limit" && value >= 0) p->tune.item_limit = value;
+    else if (k == "device_probe" && (value == 0 || value == 1)) {
+      if (value) return mirror_enable(p);
+      mirror_disable(p);
+    }
+    else return fail(p, MP_EINVAL, "unknown tunable or value out of range");
+    return MP_OK;
   }
-  else return fail(p, MP_EINVAL, "unknown tunable or value out of range");
-  return MP_OK;
+  MP_CATCH(p)
 }
 
 }  // extern "C"

@@ -15,6 +15,7 @@ from . import build as _build
 MP_TIER_HBM, MP_TIER_HOST_PINNED = 0, 1
 MP_LAYOUT_DEFAULT, MP_LAYOUT_DISCRETE, MP_LAYOUT_AGGREGATED = 0, 1, 2
 MP_OK, MP_EINVAL, MP_ESHAPE, MP_ENOMEM, MP_ENOSTAGING, MP_EHIP, MP_ESTALE = 0, -1, -2, -3, -4, -5, -6
+MP_EHOST = -7
 MP_DST_GIVEN, MP_EVICT_ON_DEMAND, MP_ASYNC = 0x01, 0x02, 0x04
 MP_MATCH_PIN, MP_TOKENS_ON_DEVICE, MP_DIRECT = 0x08, 0x10, 0x20
 MP_PER_FRAGMENT = 0x40

@@ -39,7 +39,8 @@ def test_selftest_and_strerror():
 
 def test_header_constants_match_binding():
     text = open(os.path.join(ROOT, "include", "mempool.h")).read()
-    for name in ("MP_EINVAL", "MP_ESHAPE", "MP_ENOMEM", "MP_ENOSTAGING", "MP_EHIP", "MP_ESTALE"):
+    for name in ("MP_EINVAL", "MP_ESHAPE", "MP_ENOMEM", "MP_ENOSTAGING", "MP_EHIP", "MP_ESTALE",
+                 "MP_EHOST"):
         m = re.search(rf"#define {name} \((-\d+)\)", text)
         assert int(m.group(1)) == getattr(M, name)
     for name in ("MP_DST_GIVEN", "MP_EVICT_ON_DEMAND", "MP_ASYNC", "MP_MATCH_PIN",
