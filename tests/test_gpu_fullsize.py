@@ -268,3 +268,47 @@ def test_config5_tp_share_and_host_tier(gpu):
     check_sample(geom, host, back, h_ids, b_ids, rng, k=32)
     check_sample(geom, src, back, tbl[pick], b_ids, rng, k=32)   # round trip = identity
     release(src, dst, host, back)
+
+
+@pytest.mark.parametrize("cfg,NB", [(2, 64), (3, 256), (4, 24), (5, 512)])
+@pytest.mark.parametrize("direct", [0, 1])
+def test_exact_geometry_dense_compare(gpu, cfg, NB, direct):
+    """The exact L / F of each configuration with few enough blocks (0.3-0.6 GiB a pool) that the
+    oracle holds dense copies: after batched asynchronous transfers in the default launch shape,
+    staged or fused, every byte of the destination pool, every id and the statistics agree."""
+    M, TorchPool = gpu
+    g = W.CONFIGS[cfg]
+    geom, src, dst = make_pools(gpu, g, NB, NB, staging_blocks=max(2, NB // 5))
+    o_src = O.OraclePool(*geom, NB, data=src.bytes())
+    o_dst = O.OraclePool(*geom, NB, data=dst.bytes())
+    o_src.alloc(NB)
+    rng = np.random.default_rng(1000 + cfg)
+    flags = M.MP_EVICT_ON_DEMAND | M.MP_ASYNC | (M.MP_DIRECT if direct else 0)
+    n_req = 6
+    shared = rng.integers(0, g.vocab, 2 * g.bs, dtype=np.uint32)
+    for rnd in range(3):                  # later rounds find the shared prefix and must evict
+        lens = rng.integers(1, max(2, NB // 8) * g.bs, n_req)
+        prompts = [np.concatenate([shared, rng.integers(0, g.vocab, int(n), dtype=np.uint32)])
+                   for n in lens]
+        toks, tok_off = W.csr(prompts)
+        nblk = np.array([(len(p) + g.bs - 1) // g.bs for p in prompts], np.uint32)
+        cap_off = np.concatenate([[0], np.cumsum(nblk)]).astype(np.uint32)
+        rc, mb, m = M.mp_match_batch(dst.h, toks, tok_off, cap_off, M.MP_MATCH_PIN)
+        mo = [o_dst.match(p, flags=O.MATCH_PIN)[1] for p in prompts]
+        assert rc == 0 and m.tolist() == [len(x) for x in mo]
+        blk_off = np.concatenate([[0], np.cumsum(nblk - m)]).astype(np.uint32)
+        src_tbl = rng.integers(0, NB, int(blk_off[-1])).astype(np.int32)
+        rc, d = M.mp_transfer_with_insert_batch(src.h, dst.h, toks, tok_off, m, src_tbl, blk_off, flags)
+        rco, d_o = O.transfer_with_insert_batch(o_src, o_dst, toks, tok_off, m, src_tbl, blk_off,
+                                                flags=O.EVICT_ON_DEMAND)
+        assert rc == rco, (rnd, rc, rco, M.mp_last_error(src.h))
+        ids = [mb[cap_off[r]:cap_off[r] + m[r]] for r in range(n_req)]
+        if rc == 0:
+            assert d.tolist() == d_o.tolist()
+            ids.append(d)
+        ids = np.concatenate(ids).astype(np.int32)
+        assert M.mp_free(dst.h, ids) == o_dst.free(ids) == 0
+        assert dst.stats() == o_dst.stats()
+        assert np.array_equal(dst.bytes(), o_dst.data), (cfg, rnd)
+    assert np.array_equal(src.bytes(), o_src.data)
+    release(src, dst)
