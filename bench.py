@@ -150,7 +150,14 @@ def cpu_baseline(W, geom, n_sessions=64, n_turns=4, NB_src=4096, NB_dst=8704):
         moved += int(blk_off[-1])
         hashed += int(sum(len(turn["toks"][turn["tok_off"][r]:turn["tok_off"][r + 1]]) // geom.bs
                           for r in range(n_sessions)))
+    model = ""
+    try:
+        with open("/proc/cpuinfo") as f:
+            model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "")
+    except OSError:
+        pass
     return dict(value=moved * geom.B / t_total / 1e9, unit="GB/s", cores=1, kind="oracle",
+                host_cpu=model, host_cores_visible=os.cpu_count(),
                 sample=f"config 3, the {n_turns} turns of one set of {n_sessions} sessions "
                        f"({moved} blocks = {moved * geom.B / 2**30:.2f} GiB payload, {hashed} blocks "
                        f"hashed+matched), pools reduced to {NB_src}/{NB_dst} blocks",

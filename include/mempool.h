@@ -40,7 +40,11 @@
  * ERRORS
  *   Every call returns MP_OK (0) or a negative code.  Calls are all-or-nothing: when a code
  *   other than MP_OK, MP_EHIP or MP_EHOST comes back, no pool byte, index entry, reference count or
- *   free-list entry has changed.  mp_last_error(pool) returns a text for the last failure.
+ *   free-list entry has changed.  After MP_EHIP a transfer has handed freshly allocated
+ *   destination blocks back to the free list (evictions made to find them are not undone) and
+ *   pool bytes may be partly written.  mp_last_error(pool) returns a text for the last failure.
+ *   A pool is bound to the device that is current at its first device call; keep that device
+ *   current for every later call on the pool.
  *
  * THREADS AND STREAMS
  *   One thread at a time per pool.  Device work of a transfer is enqueued on the SOURCE pool's

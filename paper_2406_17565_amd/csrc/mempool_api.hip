@@ -745,8 +745,9 @@ int twi_core(mp_pool *src, mp_pool *dst, const uint32_t *tokens, const uint32_t 
   // transmission step
   rc = run_copy(src, dst, src_blocks, dst_blocks, total, flags);
   if (rc == MP_OK) rc = finish_copy(src, dst, flags);
-  if (rc != MP_OK) {
+  if (rc != MP_OK) {  // a HIP failure: hand the fresh destination blocks back
     unpin_all();
+    if (!(flags & MP_DST_GIVEN)) (void)dst->idx.release(dst_blocks, total);
     return rc;
   }
 
@@ -1095,7 +1096,10 @@ int mp_transfer(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks, int32
       return fail(src, MP_ENOMEM, "destination pool cannot supply the blocks");
     rc = run_copy(src, dst, src_blocks, dst_blocks, n, flags);
     if (rc == MP_OK) rc = finish_copy(src, dst, flags);
-    if (rc != MP_OK) return rc;
+    if (rc != MP_OK) {  // a HIP failure: hand the fresh destination blocks back
+      if (!(flags & MP_DST_GIVEN)) (void)dst->idx.release(dst_blocks, n);
+      return rc;
+    }
     if (dst->cb) dst->cb(dst->cb_user, priv, priv_len, dst_blocks, n);
     return MP_OK;
   }
