@@ -324,3 +324,84 @@ def test_tiny_config_walkthrough():
     assert moved == [8, 4, 4, 4, 4, 4, 4, 4]          # 36 blocks, 576 KiB
     assert sum(moved) * g.B == 576 * 1024
     assert dst.stats()["n_free"] == g.NB - 36
+
+
+# ---- invariants that hold whatever the order of calls ------------------------------------------
+def test_invariants_under_random_calls():
+    """Properties the rules imply for ANY call sequence: every block is in exactly one of the
+    states free / held / historical; evict frees exactly what it reports and nothing that is
+    referenced; a pinned match stays matched; a match is never longer than the longest
+    block-aligned prefix shared with some inserted prompt, and two prompts get the same ids on
+    the prefix they share."""
+    for seed in range(8):
+        rng = np.random.default_rng(900 + seed)
+        NB = 24
+        p = pool(NB, seed)
+        inserted, pinned = [], []          # prompts ever inserted; (prompt, ids) pinned matches
+        held = []                          # id arrays this test still has to free
+        for step in range(200):
+            op = int(rng.integers(0, 6))
+            st0 = p.stats()
+            if op == 0:                                                   # insert a new prompt
+                if inserted and rng.integers(0, 2):
+                    base = inserted[int(rng.integers(0, len(inserted)))]
+                    t = np.concatenate([base[: BS * int(rng.integers(0, len(base) // BS + 1))],
+                                        rng.integers(0, 9, int(rng.integers(1, 3 * BS)), dtype=np.uint32)])
+                else:
+                    t = rng.integers(0, 9, int(rng.integers(0, 5 * BS)), dtype=np.uint32)
+                rc, ids = p.alloc(len(t) // BS, flags=O.EVICT_ON_DEMAND)
+                if rc == 0:
+                    rc2, n_new = p.insert(t, ids)
+                    assert rc2 == 0 and n_new <= len(ids)
+                    inserted.append(t)
+                    held.append(ids)
+                else:
+                    assert rc == O.ENOMEM and p.stats() == st0            # all or nothing
+            elif op == 1 and held:                                        # a request finishes
+                ids = held.pop(int(rng.integers(0, len(held))))
+                assert p.free(ids) == 0
+            elif op == 2:                                                 # evict
+                k = int(rng.integers(0, 6))
+                rc, e = p.evict(k)
+                st = p.stats()
+                assert rc == 0 and e <= k
+                assert st["n_free"] == st0["n_free"] + e and st["n_indexed"] == st0["n_indexed"] - e
+                assert st["n_held"] == st0["n_held"]
+            elif op == 3 and inserted:                                    # match with a pin
+                t = inserted[int(rng.integers(0, len(inserted)))]
+                rc, m = p.match(t, flags=O.MATCH_PIN)
+                assert rc == 0
+                pinned.append((t, m))
+                held.append(m)
+            elif op == 4 and inserted:                                    # plain match, bounds
+                t = inserted[int(rng.integers(0, len(inserted)))]
+                q = np.concatenate([t, rng.integers(0, 9, BS, dtype=np.uint32)])
+                rc, m = p.match(q)
+                lcp = 0
+                for s in inserted:
+                    c, lim = 0, min(len(s), len(q)) // BS
+                    while c < lim and np.array_equal(s[c * BS:(c + 1) * BS], q[c * BS:(c + 1) * BS]):
+                        c += 1
+                    lcp = max(lcp, c)
+                assert rc == 0 and len(m) <= lcp
+                assert len(set(m.tolist())) == len(m)
+            elif op == 5 and len(inserted) >= 2:                          # shared prefixes share ids
+                a = inserted[int(rng.integers(0, len(inserted)))]
+                b = inserted[int(rng.integers(0, len(inserted)))]
+                ma, mb = p.match(a)[1], p.match(b)[1]
+                c = 0
+                while c < min(len(ma), len(mb)) and np.array_equal(a[c * BS:(c + 1) * BS], b[c * BS:(c + 1) * BS]):
+                    assert ma[c] == mb[c]
+                    c += 1
+            st = p.stats()
+            assert st["n_free"] + st["n_held"] + st["n_historical"] == NB
+            assert st["n_historical"] <= st["n_indexed"]
+            for t, m in pinned:                                           # pins survive everything
+                if any(m is h for h in held):
+                    got = p.match(t)[1]
+                    assert got[: len(m)].tolist() == m.tolist()
+        for ids in held:
+            assert p.free(ids) == 0
+        rc, e = p.evict(NB)
+        st = p.stats()
+        assert st["n_indexed"] == 0 and st["n_free"] == NB and st["n_held"] == 0
