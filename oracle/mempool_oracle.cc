@@ -97,14 +97,20 @@ uint32_t evictable_total(const orc_pool *p) {
   return c;
 }
 
-// One eviction step: least recently used unreferenced leaf, ties by smallest block id.
-bool evict_one(orc_pool *p) {
+// The eviction rule: least recently used unreferenced leaf, ties by smallest block id.
+Node *next_victim(const orc_pool *p) {
   Node *victim = nullptr;
   for (uint32_t b = 0; b < p->NB; ++b) {
     Node *n = p->node_of[b];
     if (!n || p->ref[b] != 0 || !n->children.empty()) continue;
     if (!victim || n->last_use < victim->last_use) victim = n;  // ascending b => ties keep smaller id
   }
+  return victim;
+}
+
+// One eviction step.
+bool evict_one(orc_pool *p) {
+  Node *victim = next_victim(p);
   if (!victim) return false;
   victim->parent->children.erase(victim->key);
   p->node_of[victim->block] = nullptr;
@@ -527,6 +533,105 @@ int orc_transfer_with_insert_batch(orc_pool_t *src, orc_pool_t *dst, const uint3
   }
   for (auto &pr : prefix) for (Node *nd : pr) --dst->ref[nd->block];
   return rc;
+}
+
+// ---- swap between the two tiers of one instance -------------------------------------------
+// Table 1 names swap_out(num_blocks) and swap_in(addrList) and says no more; section 4.2 lets
+// an index node point to HBM or DRAM.  Reading of this build: the two tiers are two pools with
+// an index each; the lower tier's index stays closed under prefixes, so moving a block down
+// means caching its whole prompt prefix below (copying what is missing), and the upper tier
+// then forgets the block.  The prefix of a node is read off the trie: the edge labels from the
+// root down to it.
+namespace {
+void prefix_of(const Node *n, std::vector<uint32_t> *tokens, std::vector<int32_t> *blocks) {
+  std::vector<const Node *> chain;
+  for (const Node *a = n; a->block >= 0; a = a->parent) chain.push_back(a);
+  tokens->clear();
+  blocks->clear();
+  for (size_t i = chain.size(); i-- > 0;) {
+    tokens->insert(tokens->end(), chain[i]->key.begin(), chain[i]->key.end());
+    blocks->push_back(chain[i]->block);
+  }
+}
+
+int check_tier_pair(const orc_pool *a, const orc_pool *b) {
+  if (!a || !b || a == b) return ORC_EINVAL;
+  if (!same_geometry(a, b)) return ORC_ESHAPE;
+  if (a->tier == ORC_TIER_HOST && b->tier == ORC_TIER_HOST) return ORC_ESHAPE;
+  if (a->seed != b->seed) return ORC_EINVAL;
+  return ORC_OK;
+}
+
+// Cache the prefix (tokens, held in `from` under `blocks`) in `to`: transfer_with_insert of the
+// part `to` lacks, new blocks released at once.
+int cache_prefix(orc_pool *from, orc_pool *to, const std::vector<uint32_t> &tokens,
+                 const std::vector<int32_t> &blocks) {
+  const uint32_t d = (uint32_t)blocks.size();
+  const uint32_t m = (uint32_t)walk(to, tokens.data(), d).size();
+  std::vector<int32_t> fresh(d - m + 1);
+  int rc = orc_transfer_with_insert(from, to, tokens.data(), d * to->bs, m, blocks.data() + m,
+                                    fresh.data(), d - m, ORC_EVICT_ON_DEMAND);
+  if (rc != ORC_OK) return rc;
+  return orc_free(to, fresh.data(), d - m);
+}
+}  // namespace
+
+int orc_swap_out(orc_pool_t *upper, orc_pool_t *lower, uint32_t num_blocks, uint32_t *n_swapped) {
+  int rc = check_tier_pair(upper, lower);
+  if (rc != ORC_OK) return rc;
+  if (!n_swapped) return ORC_EINVAL;
+  uint32_t done = 0;
+  while (done < num_blocks) {
+    Node *victim = next_victim(upper);
+    if (!victim) break;
+    std::vector<uint32_t> tokens;
+    std::vector<int32_t> blocks;
+    prefix_of(victim, &tokens, &blocks);
+    rc = cache_prefix(upper, lower, tokens, blocks);
+    if (rc == ORC_ENOMEM) break;  // the lower tier is full of referenced data
+    if (rc != ORC_OK) return rc;
+    evict_one(upper);             // nothing in `upper` changed meanwhile: removes `victim`
+    ++done;
+  }
+  *n_swapped = done;
+  return ORC_OK;
+}
+
+int orc_swap_in(orc_pool_t *lower, orc_pool_t *upper, const int32_t *lower_blocks, uint32_t n,
+                int32_t *upper_blocks) {
+  int rc = check_tier_pair(lower, upper);
+  if (rc != ORC_OK) return rc;
+  if ((!lower_blocks || !upper_blocks) && n) return ORC_EINVAL;
+  std::vector<std::pair<uint32_t, uint32_t>> order;  // (depth, position)
+  for (uint32_t i = 0; i < n; ++i) {
+    if (!in_range(lower, lower_blocks[i]) || !lower->node_of[lower_blocks[i]]) return ORC_EINVAL;
+    uint32_t depth = 0;
+    for (const Node *a = lower->node_of[lower_blocks[i]]; a->block >= 0; a = a->parent) ++depth;
+    order.push_back({depth, i});
+  }
+  std::stable_sort(order.begin(), order.end(),
+                   [](const std::pair<uint32_t, uint32_t> &a, const std::pair<uint32_t, uint32_t> &b) {
+                     return a.first > b.first;
+                   });
+  std::vector<int32_t> taken;
+  for (const auto &o : order) {
+    Node *node = lower->node_of[lower_blocks[o.second]];
+    std::vector<uint32_t> tokens;
+    std::vector<int32_t> blocks;
+    prefix_of(node, &tokens, &blocks);
+    ++lower->clock;  // the prefix is used in the lower tier
+    for (Node *a = node; a->block >= 0; a = a->parent) a->last_use = lower->clock;
+    rc = cache_prefix(lower, upper, tokens, blocks);
+    if (rc != ORC_OK) {
+      orc_free(upper, taken.data(), (uint32_t)taken.size());
+      return rc;
+    }
+    const int32_t up = walk(upper, tokens.data(), (uint32_t)blocks.size()).back()->block;
+    ++upper->ref[up];
+    taken.push_back(up);
+    upper_blocks[o.second] = up;
+  }
+  return ORC_OK;
 }
 
 }  // extern "C"

@@ -15,6 +15,9 @@
  *   orc_block_hashes : composition of the two above, worked vectors under tests/golden/.
  *   orc_match / orc_insert : brute-force longest common block-aligned prefix on tiny inputs.
  *   orc_evict, orc_delete, orc_alloc / orc_free : scripted scenarios derived by hand from the rule.
+ *   orc_swap_out / orc_swap_in : a scripted scenario, and invariants that hold whatever the
+ *       conventions are -- no cached prefix is lost from the union of the two tiers, bytes are
+ *       carried unchanged, the upper tier frees exactly the blocks evict would have freed.
  *   PARITY UNPINNED against the paper: the paper fixes neither a hash function, nor the
  *   allocation order, nor an eviction policy; those three are conventions of this build
  *   and are pinned only to their own written definitions.
@@ -85,6 +88,10 @@ int orc_transfer_with_insert_batch(orc_pool_t *src, orc_pool_t *dst, const uint3
                                    const uint32_t *first_block, const int32_t *src_blocks,
                                    int32_t *dst_blocks, const uint32_t *blk_off,
                                    uint32_t flags);
+/* the two tiers of one instance: move cached blocks down (by the eviction order) / up */
+int orc_swap_out(orc_pool_t *upper, orc_pool_t *lower, uint32_t num_blocks, uint32_t *n_swapped);
+int orc_swap_in(orc_pool_t *lower, orc_pool_t *upper, const int32_t *lower_blocks, uint32_t n,
+                int32_t *upper_blocks);
 #ifdef __cplusplus
 }
 #endif

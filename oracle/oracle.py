@@ -62,6 +62,8 @@ def lib():
                                                C.c_uint32, C.c_uint32]
         L.orc_transfer_with_insert_batch.argtypes = [vp, vp, vp, vp, C.c_uint32, vp, vp, vp, vp,
                                                      C.c_uint32]
+        L.orc_swap_out.argtypes = [vp, vp, C.c_uint32, u32p]
+        L.orc_swap_in.argtypes = [vp, vp, vp, C.c_uint32, vp]
         _lib = L
     return _lib
 
@@ -215,3 +217,16 @@ def transfer_with_insert_batch(src, dst, tokens, tok_off, first_block, src_block
                                               fb.size, _ptr(fb), _ptr(s), _ptr(d),
                                               bo.ctypes.data_as(C.c_void_p), flags)
     return rc, d
+
+
+def swap_out(upper: OraclePool, lower: OraclePool, num_blocks):
+    n = C.c_uint32(0)
+    rc = lib().orc_swap_out(upper.h, lower.h, num_blocks, C.byref(n))
+    return rc, n.value
+
+
+def swap_in(lower: OraclePool, upper: OraclePool, lower_blocks):
+    b = _i32(lower_blocks)
+    out = np.full(b.size, -1, dtype=np.int32)
+    rc = lib().orc_swap_in(lower.h, upper.h, _ptr(b), b.size, _ptr(out))
+    return rc, out

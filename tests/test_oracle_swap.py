@@ -1,0 +1,187 @@
+"""Pins for the oracle's swap_out / swap_in between the two tiers of one instance (Table 1 of
+the paper names the two calls; which blocks move and how the lower tier is indexed are this
+build's conventions).  A hand-derived script fixes the conventions; the random tests check
+what must hold under ANY convention: nothing cached is lost from the union of the tiers, bytes
+arrive unchanged, and the upper tier frees exactly what evict would have freed."""
+import numpy as np
+
+from oracle import oracle as O
+from paper_2406_17565_amd import workloads as W
+
+GEOM = (2, 1, 8, 4, 2)  # L, H, D, bs, e -> F = 64 bytes, B = 256
+BS = 4
+
+
+def pool(NB, data_seed, tier=O.TIER_HBM, **kw):
+    rng = np.random.default_rng(data_seed)
+    L, H, D, bs, e = GEOM
+    return O.OraclePool(*GEOM, NB, tier=tier, data=W.kv_bytes(rng, 2 * L * NB * bs * H * D * e), **kw)
+
+
+def records(p, ids):
+    return p.gather(ids).reshape(len(ids), p.B)
+
+
+def test_script():
+    up, low = pool(8, 1), pool(8, 2, tier=O.TIER_HOST)
+    A = np.arange(0, 3 * BS, dtype=np.uint32)                                    # a0 a1 a2
+    Bq = np.concatenate([A[:BS], np.arange(100, 100 + BS, dtype=np.uint32)])     # a0 b1
+    _, a = up.alloc(3)
+    up.insert(A, a)                 # up clock 1: nodes 0,1,2
+    _, b = up.alloc(2)              # 3,4; a0 exists, so 3 is not adopted
+    up.insert(Bq, b)                # up clock 2: touches 0, creates 4
+    up.free(a)
+    up.free(b)                      # 3 goes back to the free list
+    orig = records(up, np.arange(8))
+    # leaves: 2 (last use 1), 4 (last use 2) -> 2 moves first, and with it its whole prefix
+    assert O.swap_out(up, low, 1) == (0, 1)
+    assert low.stats()["n_indexed"] == 3 and low.stats()["n_historical"] == 3
+    assert np.array_equal(records(low, [0, 1, 2]), orig[[0, 1, 2]])              # a fresh pool hands out 0,1,2
+    assert up.stats()["n_indexed"] == 3 and up.stats()["n_free"] == 5
+    # next: leaf 1 (last use 1; its prefix is already below: no copy), then leaf 4 (prefix a0 is below)
+    assert O.swap_out(up, low, 2) == (0, 2)
+    assert low.stats()["n_indexed"] == 4
+    assert np.array_equal(records(low, [3]), orig[[4]])
+    assert low.match(Bq)[1].tolist() == [0, 3] and low.match(A)[1].tolist() == [0, 1, 2]
+    assert up.match(A)[1].tolist() == [0] and up.match(Bq)[1].tolist() == [0]
+    # bring b1 back: upper free stack is ... 3, 2, 1, 4 -> block 4 is handed out again
+    rc, got = O.swap_in(low, up, [3])
+    assert rc == 0 and got.tolist() == [4]
+    assert up.match(Bq)[1].tolist() == [0, 4]
+    assert np.array_equal(records(up, [0, 4]), orig[[0, 4]])
+    assert up.evict(10) == (0, 0)                       # 4 is referenced, 0 has a child
+    assert up.free(got) == 0
+    assert up.evict(10) == (0, 2)
+    assert low.match(Bq)[1].tolist() == [0, 3]          # the lower tier keeps its copy
+
+
+def test_errors_and_limits():
+    up, low = pool(4, 3), pool(2, 4, tier=O.TIER_HOST)
+    assert O.swap_out(up, up, 1)[0] == O.EINVAL
+    other = O.OraclePool(3, 1, 8, 4, 2, 4)
+    assert O.swap_out(up, other, 1)[0] == O.ESHAPE
+    low2 = pool(2, 5, tier=O.TIER_HOST)
+    assert O.swap_out(low, low2, 1)[0] == O.ESHAPE                    # host to host
+    seeded = pool(4, 6, tier=O.TIER_HOST, seed=9)
+    assert O.swap_out(up, seeded, 1)[0] == O.EINVAL                   # two tiers of one instance share the seed
+    assert O.swap_out(up, low, 3) == (0, 0)                           # nothing cached yet
+    t = np.arange(3 * BS, dtype=np.uint32)
+    _, a = up.alloc(3)
+    up.insert(t, a)
+    assert O.swap_out(up, low, 3) == (0, 0)                           # everything referenced
+    up.free(a)
+    # the leaf's prefix needs 3 blocks below, the lower pool has 2: nothing moves, nothing is lost
+    assert O.swap_out(up, low, 3) == (0, 0)
+    assert up.match(t)[1].tolist() == a.tolist() and low.stats()["n_indexed"] == 0
+    assert O.swap_in(low, up, [0])[0] == O.EINVAL                     # block 0 of `low` is not indexed
+    assert O.swap_in(low, up, [5])[0] == O.EINVAL
+    # swap_in into an upper tier that cannot supply blocks
+    low3 = pool(4, 7, tier=O.TIER_HOST)
+    assert O.swap_out(up, low3, 3) == (0, 3)
+    _, hold = up.alloc(4)                                             # upper tier fully held
+    st = up.stats()
+    rc, _ = O.swap_in(low3, up, low3.match(t)[1])
+    assert rc == O.ENOMEM and up.stats() == st
+
+
+def test_swap_out_frees_what_evict_would_free():
+    for seed in range(6):
+        rng = np.random.default_rng(300 + seed)
+        a_up, b_up = pool(20, seed), pool(20, seed)
+        low = pool(64, 50 + seed, tier=O.TIER_HOST)
+        held = []
+        for step in range(120):
+            op = int(rng.integers(0, 4))
+            if op == 0:
+                t = rng.integers(0, 5, int(rng.integers(0, 5 * BS)), dtype=np.uint32)
+                rc, ids = a_up.alloc(len(t) // BS)
+                rc2, ids2 = b_up.alloc(len(t) // BS)
+                assert rc == rc2 and ids.tolist() == ids2.tolist()
+                if rc == 0:
+                    assert a_up.insert(t, ids) == b_up.insert(t, ids)
+                    held.append(ids)
+            elif op == 1 and held:
+                ids = held.pop(int(rng.integers(0, len(held))))
+                assert a_up.free(ids) == b_up.free(ids) == 0
+            elif op == 2:
+                k = int(rng.integers(0, 5))
+                assert O.swap_out(a_up, low, k) == b_up.evict(k)
+            else:
+                t = rng.integers(0, 5, 3 * BS, dtype=np.uint32)
+                assert a_up.match(t)[1].tolist() == b_up.match(t)[1].tolist()
+            assert a_up.stats() == b_up.stats()
+        n = a_up.stats()["n_free"]
+        assert a_up.alloc(n)[1].tolist() == b_up.alloc(n)[1].tolist()    # same free-list order
+
+
+def test_nothing_cached_is_lost_and_bytes_are_unchanged():
+    for seed in range(6):
+        rng = np.random.default_rng(400 + seed)
+        up, low = pool(16, seed), pool(96, 70 + seed, tier=O.TIER_HOST)   # low never has to evict
+        content = {}                  # prompt prefix (tuple of tokens) -> the record cached for it
+        prompts, held = [], []
+
+        def coverage(t):
+            return max(len(up.match(t)[1]), len(low.match(t)[1]))
+
+        def check_all():
+            for t in prompts:
+                for tier in (up, low):
+                    ids = tier.match(t)[1]
+                    rec = records(tier, ids)
+                    for i in range(len(ids)):
+                        assert np.array_equal(rec[i], content[tuple(int(x) for x in t[: (i + 1) * BS])])
+
+        for step in range(150):
+            op = int(rng.integers(0, 5))
+            if op == 0 and len(prompts) < 40:
+                if prompts and rng.integers(0, 2):
+                    base = prompts[int(rng.integers(0, len(prompts)))]
+                    t = np.concatenate([base[: BS * int(rng.integers(0, len(base) // BS + 1))],
+                                        rng.integers(0, 7, int(rng.integers(BS, 3 * BS)), dtype=np.uint32)])
+                else:
+                    t = rng.integers(0, 7, int(rng.integers(BS, 4 * BS)), dtype=np.uint32)
+                nb = len(t) // BS
+                if up.stats()["n_free"] < nb:
+                    O.swap_out(up, low, nb)
+                rc, ids = up.alloc(nb)
+                if rc != 0:
+                    continue
+                # the "engine" fills its new blocks before inserting them; KV is a function of
+                # the prefix, so the bytes for one prefix are the same whenever it is computed
+                for i in range(nb):
+                    key = tuple(int(x) for x in t[: (i + 1) * BS])
+                    if key not in content:
+                        content[key] = W.kv_bytes(np.random.default_rng(abs(hash(key)) % 2**32), up.B)
+                    up.scatter([ids[i]], content[key])
+                up.insert(t, ids)
+                prompts.append(t)
+                held.append(ids)
+            elif op == 1 and held:
+                assert up.free(held.pop(int(rng.integers(0, len(held))))) == 0
+            elif op == 2:
+                before = [coverage(t) for t in prompts]
+                rc, n = O.swap_out(up, low, int(rng.integers(0, 6)))
+                assert rc == 0
+                assert [coverage(t) for t in prompts] == before
+            elif op == 3 and prompts:
+                t = prompts[int(rng.integers(0, len(prompts)))]
+                ids = low.match(t)[1]
+                if len(ids) == 0:
+                    continue
+                pick = ids[rng.permutation(len(ids))[: int(rng.integers(1, len(ids) + 1))]]
+                before = coverage(t)
+                rc, got = O.swap_in(low, up, pick)
+                if rc == 0:
+                    # entry i is the upper block caching the same prefix block as lower block pick[i]
+                    upm = up.match(t)[1]
+                    for lb, ub in zip(pick, got):
+                        depth = ids.tolist().index(lb)
+                        assert upm[depth] == ub
+                        assert np.array_equal(records(up, [ub]), records(low, [lb]))
+                    assert up.free(got) == 0
+                    # (making room above may drop OTHER prompts that were never moved down)
+                    assert coverage(t) >= before
+                else:
+                    assert rc == O.ENOMEM
+            check_all()
