@@ -197,6 +197,36 @@ def host_tier(args):
             assert rc == 0, M.mp_last_error(host.h)
             assert M.mp_free(host.h, h) == 0
         res[name] = (min(out_t[1:]), min(in_t[1:]))
+    # swap_out / swap_in (Table 1) between the two tiers of one instance: a cache of 32 prompts of
+    # 2048 tokens moves down, coldest leaf first, and comes back prompt by prompt in one call
+    up = TorchPool(*geom, n, staging_blocks=512)
+    low = TorchPool(*geom, n, tier=M.MP_TIER_HOST_PINNED)
+    up.mem.view(torch.int32).random_()
+    torch.cuda.synchronize()
+    prompts = W.random_prompts(55, [2048] * 32, g.vocab)
+    swap = {}
+    for name, fl in (("copy_engine", 0), ("zero_copy_kernel", M.MP_DIRECT)):
+        for p in prompts:
+            rc, ids = M.mp_alloc(up.h, 128)
+            assert rc == 0 and M.mp_insert(up.h, p, ids)[0] == 0 and M.mp_free(up.h, ids) == 0
+        t0 = time.perf_counter()
+        rc, moved = M.mp_swap_out(up.h, low.h, n, fl)
+        t_out = time.perf_counter() - t0
+        assert rc == 0 and moved == n, M.mp_last_error(up.h)
+        low_ids = np.concatenate([M.mp_match(low.h, p, 128)[1] for p in prompts])
+        assert low_ids.size == n
+        t0 = time.perf_counter()
+        rc, up_ids = M.mp_swap_in(low.h, up.h, low_ids, fl)
+        t_in = time.perf_counter() - t0
+        assert rc == 0, M.mp_last_error(low.h)
+        swap[name] = {"swap_out_GBs": round(n * g.B / t_out / 1e9, 2),
+                      "swap_in_GBs": round(n * g.B / t_in / 1e9, 2),
+                      "swap_out_us_per_block": round(t_out / n * 1e6, 2),
+                      "swap_in_us_per_block": round(t_in / n * 1e6, 2)}
+        assert M.mp_free(up.h, up_ids) == 0                   # empty both caches for the next flavour
+        assert M.mp_evict(up.h, n) == (0, n) and M.mp_evict(low.h, n) == (0, n)
+    up.close()
+    low.close()
     # yardstick: one plain copy of the same bytes between a device tensor and pinned memory
     dev = src.staging[: min(src.staging.numel(), 1 << 30)]
     pin = host.mem[: dev.numel()]
@@ -220,6 +250,7 @@ def host_tier(args):
         "hbm_to_host": {k: round(v[0], 2) for k, v in rate.items()},
         "host_to_hbm": {k: round(v[1], 2) for k, v in rate.items()},
         "plain_pinned_copy": {k: round(v, 2) for k, v in plain.items()},
+        "swap": swap,
         "n_gpus": 1, "dtype": "u8", "data": "synthetic",
         "config": {"workload": f"config 5 ({g.name}): {n} blocks ({payload / 2**30:.2f} GiB) per "
                                f"transfer; copy_engine = gather + hipMemcpyAsync through two 160 MiB "

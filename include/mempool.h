@@ -208,6 +208,37 @@ int mp_transfer_with_insert_batch(mp_pool_t *src, mp_pool_t *dst, const uint32_t
                                   const uint32_t *blk_off /* n_req+1 into both tables */,
                                   uint32_t flags);
 
+/* swap_out (Table 1: "swap a given number of blocks from HBM to DRAM"; section 4.2: index
+ * nodes may point to HBM or DRAM).  `upper` and `lower` are two pools of one instance (same
+ * geometry and hash_seed, else MP_ESHAPE / MP_EINVAL), normally an HBM pool and a pinned-host
+ * pool.  Up to num_blocks times: take the block mp_evict(upper) would take next (least recently
+ * used unreferenced leaf); make sure its whole prompt prefix is cached in `lower` -- the part
+ * `lower` lacks is copied there and indexed exactly as by mp_transfer_with_insert(upper ->
+ * lower, that prefix, MP_EVICT_ON_DEMAND) followed by mp_free of the new lower blocks, so they
+ * are historical at once; ancestors that stay cached in `upper` are then cached in both --;
+ * then drop the block from upper's index and free it.  Cached data is never lost: whatever
+ * matched in `upper` before still matches in `upper` or `lower` afterwards, unless `lower`
+ * itself had to evict.  Stops early, without error, when `upper` has no victim left or `lower`
+ * cannot supply blocks; *n_swapped_out = blocks freed in `upper` (their ids are pushed on the
+ * free list in that order).  The copies of all victims share launches and have completed on
+ * return (MP_ASYNC is ignored); MP_DIRECT selects the fused / zero-copy kernel.  After MP_EHIP
+ * the cached content of `lower` is undefined. */
+int mp_swap_out(mp_pool_t *upper, mp_pool_t *lower, uint32_t num_blocks, uint32_t flags,
+                uint32_t *n_swapped_out);
+
+/* swap_in (Table 1: "swap blocks with given address from DRAM to HBM"; section 8.3: historical
+ * KV that sits in DRAM is swapped into HBM before prefill uses it).  lower_blocks: n ids that
+ * are indexed in `lower` (what mp_match(lower) returned).  For every id, deepest prefix first
+ * (ties: list order): the prefix counts as used in `lower` (one clock tick, path touched); the
+ * part of it that `upper` lacks is copied up and indexed as by mp_transfer_with_insert(lower ->
+ * upper, that prefix, MP_EVICT_ON_DEMAND) followed by mp_free of the new blocks; then
+ * upper_blocks_out[i] = the block of `upper` that now caches the same prefix block, with ONE
+ * reference taken for the caller (release with mp_free).  `lower` keeps its copy.  On MP_ENOMEM
+ * (upper cannot supply blocks) the references taken so far are dropped again; blocks already
+ * brought up stay cached. */
+int mp_swap_in(mp_pool_t *lower, mp_pool_t *upper, const int32_t *lower_blocks, uint32_t n,
+               int32_t *upper_blocks_out, uint32_t flags);
+
 /* Chained block hashes of one prompt (section 4.2 index key; the hash itself is this
  * library's convention): out[i] for i < floor(n_tokens/bs), computed by the device kernel. */
 int mp_block_hashes(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, uint64_t *out,

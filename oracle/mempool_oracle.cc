@@ -4,8 +4,8 @@
 // the GPU library is compared against.  It shares no code with that library.
 //
 // Sources in the MemServe paper:
-//   * Table 1 (MemPool API): alloc_mem, free_mem, insert, match, transfer,
-//     transfer_with_insert; Table 3 adds evict.
+//   * Table 1 (MemPool API): alloc_mem, free_mem, insert, match, delete, swap_out, swap_in,
+//     transfer, transfer_with_insert; Table 3 adds evict.
 //   * Section 4.2 (Indexing): a token-keyed radix tree whose nodes have the engine's block
 //     granularity, may reference HBM or DRAM, and carry an instance id.  Written here as a
 //     trie with one node per block of bs tokens.

@@ -759,6 +759,81 @@ int twi_core(mp_pool *src, mp_pool *dst, const uint32_t *tokens, const uint32_t 
   return MP_OK;
 }
 
+// ---- swap between the two tiers of one instance ------------------------------------------------
+// Both directions cache a prompt prefix that one pool holds in the other pool.  The index work
+// is done call by call in the defined order; the copies are collected and share launches.
+struct TierMove {
+  TierMove(mp_pool *f, mp_pool *t, uint32_t fl) : from(f), to(t), flags(fl) {}
+  mp_pool *from, *to;
+  uint32_t flags;
+  std::vector<int32_t> src, dst;  // pending copies: block src[i] of `from` -> block dst[i] of `to`
+  std::vector<uint32_t> tokens;
+  std::vector<uint64_t> hashes;
+  std::vector<int32_t> path, ids, fresh;
+};
+
+int tier_pair_ok(mp_pool *a, mp_pool *b) {
+  if (!a || !b || a == b) return fail(a, MP_EINVAL, "swap needs two different pools");
+  if (!same_geometry(a, b)) return fail(a, MP_ESHAPE, "the two tiers differ in geometry");
+  if (a->desc.tier != MP_TIER_HBM && b->desc.tier != MP_TIER_HBM)
+    return fail(a, MP_ESHAPE, "host-to-host transfers are not supported");
+  if (a->desc.hash_seed != b->desc.hash_seed)
+    return fail(a, MP_EINVAL, "the two tiers of one instance must share hash_seed");
+  return MP_OK;
+}
+
+int flush_moves(TierMove &mv) {
+  if (mv.src.empty()) return MP_OK;
+  const int rc = run_copy(mv.from, mv.to, mv.src.data(), mv.dst.data(), (uint32_t)mv.src.size(),
+                          mv.flags & MP_DIRECT);
+  mv.src.clear();
+  mv.dst.clear();
+  return rc;
+}
+
+// Makes `to` cache the prefix that ends in block `leaf` of `from`: the index part of
+// transfer_with_insert(from -> to, prefix, first_block = what `to` already has,
+// MP_EVICT_ON_DEMAND) followed by a release of the new blocks; the copies are only queued.
+// The chained hashes are the ones `from` keeps in its nodes (same seed, same prefix).
+// *last_out = the block of `to` that caches the prefix's last block, referenced once if
+// `keep_last`.  MP_ENOMEM changes nothing.
+int cache_prefix(TierMove &mv, int32_t leaf, bool keep_last, int32_t *last_out) {
+  PoolIndex &fi = mv.from->idx, &ti = mv.to->idx;
+  const uint32_t bs = mv.to->desc.block_size;
+  fi.path_to(leaf, mv.path);
+  const uint32_t d = (uint32_t)mv.path.size();
+  mv.tokens.resize((size_t)d * bs);
+  mv.hashes.resize(d);
+  for (uint32_t i = 0; i < d; ++i) {
+    std::memcpy(&mv.tokens[(size_t)i * bs], fi.tokens_of(mv.path[i]), 4ull * bs);
+    mv.hashes[i] = fi.hash_of(mv.path[i]);
+  }
+  mv.ids.assign(d, kNoBlock);
+  const uint32_t m = ti.walk(mv.tokens.data(), mv.hashes.data(), d, mv.ids.data());
+  const uint32_t need = d - m;
+  mv.fresh.resize(need);
+  if (need > ti.n_free()) {
+    // eviction may hand out a block that a queued copy still targets: run the queue first
+    const int rc = flush_moves(mv);
+    if (rc != MP_OK) return rc;
+  }
+  for (uint32_t i = 0; i < m; ++i) ti.pin(mv.ids[i]);
+  const bool ok = ti.alloc(need, mv.fresh.data(), true);
+  for (uint32_t i = 0; i < m; ++i) ti.unpin(mv.ids[i]);
+  if (!ok) return fail(mv.from, MP_ENOMEM, "the other tier cannot supply the blocks");
+  for (uint32_t i = 0; i < need; ++i) mv.ids[m + i] = mv.fresh[i];
+  ti.insert(mv.tokens.data(), mv.hashes.data(), d, mv.ids.data());
+  if (keep_last && d) ti.pin(mv.ids[d - 1]);
+  (void)ti.release(mv.fresh.data(), need);
+  for (uint32_t i = 0; i < need; ++i)
+    if (!ti.is_free(mv.fresh[i])) {  // (a 64-bit hash collision would leave a block un-indexed)
+      mv.src.push_back(mv.path[m + i]);
+      mv.dst.push_back(mv.fresh[i]);
+    }
+  if (last_out) *last_out = d ? mv.ids[d - 1] : kNoBlock;
+  return MP_OK;
+}
+
 }  // namespace
 
 // =============================================================================================
@@ -1170,6 +1245,82 @@ int mp_transfer_with_insert_batch(mp_pool_t *src, mp_pool_t *dst, const uint32_t
                     flags, nullptr, 0);
   }
   MP_CATCH(src)
+}
+
+int mp_swap_out(mp_pool_t *upper, mp_pool_t *lower, uint32_t num_blocks, uint32_t flags,
+                uint32_t *n_swapped_out) {
+  try {
+    int rc = tier_pair_ok(upper, lower);
+    if (rc != MP_OK) return rc;
+    if (!n_swapped_out) return fail(upper, MP_EINVAL, "null argument");
+    *n_swapped_out = 0;
+    if (num_blocks == 0 || upper->idx.next_victim() == kNoBlock) return MP_OK;
+    if ((rc = check_copy_feasible(upper, lower, 1, flags)) != MP_OK) return rc;
+    TierMove mv(upper, lower, flags);
+    std::vector<int32_t> freed;  // victims: out of the index, kept off the free list until copied
+    while (freed.size() < num_blocks) {
+      const int32_t victim = upper->idx.next_victim();
+      if (victim == kNoBlock) break;
+      rc = cache_prefix(mv, victim, false, nullptr);
+      if (rc == MP_ENOMEM) {  // the lower tier is full of referenced data: not an error
+        rc = MP_OK;
+        break;
+      }
+      if (rc != MP_OK) break;
+      freed.push_back(upper->idx.evict_next_held());
+    }
+    if (rc == MP_OK) rc = flush_moves(mv);
+    if (rc == MP_OK) rc = finish_copy(upper, lower, 0);
+    (void)upper->idx.release(freed.data(), (uint32_t)freed.size());
+    *n_swapped_out = (uint32_t)freed.size();
+    return rc;
+  }
+  MP_CATCH(upper)
+}
+
+int mp_swap_in(mp_pool_t *lower, mp_pool_t *upper, const int32_t *lower_blocks, uint32_t n,
+               int32_t *upper_blocks_out, uint32_t flags) {
+  try {
+    int rc = tier_pair_ok(lower, upper);
+    if (rc != MP_OK) return rc;
+    if ((!lower_blocks || !upper_blocks_out) && n) return fail(lower, MP_EINVAL, "null block list");
+    for (uint32_t i = 0; i < n; ++i)
+      if (!lower->idx.in_range(lower_blocks[i]) || !lower->idx.indexed(lower_blocks[i]))
+        return fail(lower, MP_EINVAL, "block id out of range or not in the lower tier's index");
+    if (n == 0) return MP_OK;
+    if ((rc = check_copy_feasible(lower, upper, 1, flags)) != MP_OK) return rc;
+    TierMove mv(lower, upper, flags);
+    // deepest prefix first, so that one copy brings up a whole chain and its ancestors only
+    // need a reference
+    std::vector<std::pair<uint32_t, uint32_t>> order(n);  // (depth, position)
+    for (uint32_t i = 0; i < n; ++i) {
+      lower->idx.path_to(lower_blocks[i], mv.path);
+      order[i] = {(uint32_t)mv.path.size(), i};
+    }
+    std::stable_sort(order.begin(), order.end(),
+                     [](const std::pair<uint32_t, uint32_t> &a, const std::pair<uint32_t, uint32_t> &b) {
+                       return a.first > b.first;
+                     });
+    std::vector<int32_t> taken;
+    for (const auto &o : order) {
+      const int32_t b = lower_blocks[o.second];
+      lower->idx.path_to(b, mv.path);
+      lower->idx.tick();  // the prefix is used in the lower tier
+      lower->idx.touch(mv.path.data(), (uint32_t)mv.path.size());
+      int32_t up = kNoBlock;
+      rc = cache_prefix(mv, b, true, &up);
+      if (rc != MP_OK) break;
+      taken.push_back(up);
+      upper_blocks_out[o.second] = up;
+    }
+    if (rc == MP_OK) rc = flush_moves(mv);
+    else (void)flush_moves(mv);  // what was indexed so far must still receive its bytes
+    const int rc2 = finish_copy(lower, upper, 0);
+    if (rc == MP_OK) rc = rc2;
+    if (rc != MP_OK) (void)upper->idx.release(taken.data(), (uint32_t)taken.size());
+    return rc;
+  }
+  MP_CATCH(lower)
 }
 
 int mp_gather(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags) {

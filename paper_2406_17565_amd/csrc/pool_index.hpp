@@ -290,23 +290,31 @@ class PoolIndex {
   uint32_t evict(uint32_t k) {
     uint32_t done = 0;
     while (done < k && !lru_.empty()) {
-      int32_t b = lru_.begin()->second;
-      lru_.erase(lru_.begin());
-      in_lru_[b] = 0;
-      table_.erase(hash_[b]);
-      indexed_[b] = 0;
-      --n_indexed_;
-      int32_t par = parent_[b];
-      parent_[b] = kNoBlock;
-      if (par != kNoBlock) {
-        --n_children_[par];
-        refresh_lru(par);
-      }
-      free_.push_back(b);
+      free_.push_back(unindex_victim());
       ++done;
     }
     return done;
   }
+
+  // The block evict() would take next, or kNoBlock.
+  int32_t next_victim() const { return lru_.empty() ? kNoBlock : lru_.begin()->second; }
+
+  // Evicts next_victim() from the index but keeps the block out of the free list, held by one
+  // reference: its bytes stay valid until the caller releases it (swap-out copies them first).
+  int32_t evict_next_held() {
+    const int32_t b = unindex_victim();
+    ref_[b] = 1;
+    return b;
+  }
+
+  // Block ids from the root of the tree down to indexed block b.
+  void path_to(int32_t b, std::vector<int32_t> &out) const {
+    out.clear();
+    for (int32_t a = b; a != kNoBlock; a = parent_[a]) out.push_back(a);
+    for (size_t i = 0, j = out.size(); i + 1 < j; ++i, --j) std::swap(out[i], out[j - 1]);
+  }
+  const uint32_t *tokens_of(int32_t b) const { return &tokens_[(size_t)b * bs_]; }
+  uint64_t hash_of(int32_t b) const { return hash_[b]; }
 
   // delete: drop the prompt's own cached blocks -- from the deepest matched node upwards,
   // every node that is an unreferenced leaf; stops at the first node that is shared (has other
@@ -353,6 +361,24 @@ class PoolIndex {
   uint32_t node_tier(int32_t b) const { return node_tier_[b]; }
 
  private:
+  // removes the least recently used unreferenced leaf from the index; the caller decides
+  // where the block goes
+  int32_t unindex_victim() {
+    const int32_t b = lru_.begin()->second;
+    lru_.erase(lru_.begin());
+    in_lru_[b] = 0;
+    table_.erase(hash_[b]);
+    indexed_[b] = 0;
+    --n_indexed_;
+    const int32_t par = parent_[b];
+    parent_[b] = kNoBlock;
+    if (par != kNoBlock) {
+      --n_children_[par];
+      refresh_lru(par);
+    }
+    return b;
+  }
+
   // keep `lru_` equal to { (last_use, b) : b indexed, unreferenced, childless }
   void refresh_lru(int32_t b) {
     if (in_lru_[b]) {

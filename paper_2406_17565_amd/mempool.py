@@ -29,6 +29,7 @@ EXPORTS = [
     "mp_set_recv_callback", "mp_profile_enable", "mp_profile_read", "mp_set_tunable",
     "mp_selftest", "mp_plain_copy", "mp_transfer_layers",
     "mp_block_hashes_batch", "mp_delete", "mp_delete_hashed", "mp_transfer_batch",
+    "mp_swap_out", "mp_swap_in",
 ]
 
 
@@ -84,6 +85,8 @@ def lib():
             "mp_block_hashes_batch": [vp, vp, vp, u32, vp, u32],
             "mp_insert_hashed": [vp, vp, u32, vp, vp, u32, u32, C.POINTER(u32)],
             "mp_match_hashed": [vp, vp, u32, vp, vp, u32, C.POINTER(u32), u32],
+            "mp_swap_out": [vp, vp, u32, u32, C.POINTER(u32)],
+            "mp_swap_in": [vp, vp, vp, u32, vp, u32],
             "mp_gather": [vp, vp, u32, u32],
             "mp_scatter": [vp, vp, u32, u32],
             "mp_set_recv_callback": [vp, RECV_CB, vp],
@@ -292,6 +295,19 @@ def mp_match_hashed(p, tokens, hashes, cap, flags=0):
     m = C.c_uint32(0)
     rc = lib().mp_match_hashed(p, _ptr(t), t.size, _ptr(h), _ptr(out), cap, C.byref(m), flags)
     return rc, out[: m.value].copy()
+
+
+def mp_swap_out(upper, lower, num_blocks, flags=0):
+    n = C.c_uint32(0)
+    rc = lib().mp_swap_out(upper, lower, num_blocks, flags, C.byref(n))
+    return rc, n.value
+
+
+def mp_swap_in(lower, upper, lower_blocks, flags=0):
+    b = _i32(lower_blocks)
+    out = np.full(b.size, -1, dtype=np.int32)
+    rc = lib().mp_swap_in(lower, upper, _ptr(b), b.size, _ptr(out), flags)
+    return rc, out
 
 
 def mp_gather(p, tbl, flags=0):

@@ -251,6 +251,8 @@ def test_config5_tp_share_and_host_tier(gpu):
     assert dst.stats() == mir.dst.stats()
     rc, mb, m = M.mp_match_batch(dst.h, toks, tok_off, blk_off)
     assert rc == 0 and m.tolist() == [128] * 256 and mb.tolist() == d.tolist()
+    for p in prompts:
+        mir.dst.match(p)
 
     # host tier: 2048 blocks (1.25 GiB) out to pinned memory and back in
     host = TorchPool(*geom, 2048, tier=M.MP_TIER_HOST_PINNED)
@@ -267,7 +269,35 @@ def test_config5_tp_share_and_host_tier(gpu):
     assert rc == 0, M.mp_last_error(host.h)
     check_sample(geom, host, back, h_ids, b_ids, rng, k=32)
     check_sample(geom, src, back, tbl[pick], b_ids, rng, k=32)   # round trip = identity
-    release(src, dst, host, back)
+
+    # swap: the receiver's cache moves its 1500 coldest blocks down to a host pool (zero-copy
+    # kernel), then one prompt is brought back up
+    assert M.mp_free(dst.h, d) == mir.dst.free(d) == 0
+    low = TorchPool(*geom, 4096, tier=M.MP_TIER_HOST_PINNED)
+    o_low = O.OraclePool(1, 1, 8, g.bs, 1, 4096, tier=O.TIER_HOST)
+    assert M.mp_swap_out(dst.h, low.h, 1500, M.MP_DIRECT) == O.swap_out(mir.dst, o_low, 1500) == (0, 1500)
+    assert dst.stats() == mir.dst.stats() and low.stats() == o_low.stats()
+    hit = [r for r in range(256) if len(o_low.match(prompts[r])[1])]
+    assert hit == [r for r in range(256) if len(M.mp_match(low.h, prompts[r], 128)[1])]
+    assert len(hit) == 12                                        # 11 whole prompts and part of a 12th
+    for r in (hit[0], hit[-1]):
+        rc, low_ids = M.mp_match(low.h, prompts[r], 128)
+        assert rc == 0 and low_ids.tolist() == o_low.match(prompts[r])[1].tolist() and len(low_ids) == 128
+        sl = tbl[r * 128:(r + 1) * 128]
+        check_sample(geom, src, low, sl, low_ids, rng, k=32)     # src -> dst -> host tier, bytes intact
+    r = hit[0]
+    assert len(M.mp_match(dst.h, prompts[r], 128)[1]) == len(mir.dst.match(prompts[r])[1]) == 0
+    low_ids = M.mp_match(low.h, prompts[r], 128)[1]
+    assert low_ids.tolist() == o_low.match(prompts[r])[1].tolist()
+    rc, up = M.mp_swap_in(low.h, dst.h, low_ids, M.MP_DIRECT)
+    rco, up_o = O.swap_in(o_low, mir.dst, low_ids)
+    assert rc == rco == 0 and up.tolist() == up_o.tolist(), M.mp_last_error(low.h)
+    assert M.mp_match(dst.h, prompts[r], 128)[1].tolist() == up.tolist()
+    mir.dst.match(prompts[r])
+    check_sample(geom, src, dst, tbl[r * 128:(r + 1) * 128], up, rng, k=32)
+    assert M.mp_free(dst.h, up) == mir.dst.free(up) == 0
+    assert dst.stats() == mir.dst.stats() and low.stats() == o_low.stats()
+    release(src, dst, host, back, low)
 
 
 @pytest.mark.parametrize("cfg,NB", [(2, 64), (3, 256), (4, 24), (5, 512)])

@@ -698,3 +698,113 @@ def test_device_probe_switched_on_late_and_long_prompts(gpu):
     assert M.mp_set_tunable(g.h, "device_probe", 0) == 0
     assert M.mp_match(g.h, long_a, 2500)[1].tolist() == o.match(long_a)[1].tolist()
     g.close()
+
+
+# ---- swap between the two tiers of one instance (Table 1: swap_out / swap_in) -------------------
+@pytest.mark.parametrize("lower_tier,direct", [(1, 0), (1, 1), (0, 0)])
+def test_swap_script(gpu, lower_tier, direct):
+    """The hand-derived scenario the oracle is pinned to, step by step on the GPU."""
+    M, TorchPool = gpu
+    geom = GEOMS["tiny"]
+    bs = geom[3]
+    fl = M.MP_DIRECT if direct else 0
+    uo, ug = make_pair(gpu, geom, 8, 1, staging_blocks=2)                 # two records: forces rounds
+    lo, lg = make_pair(gpu, geom, 8, 2, staging_blocks=0 if lower_tier else 2, tier=lower_tier)
+    A = np.arange(0, 3 * bs, dtype=np.uint32)
+    Bq = np.concatenate([A[:bs], np.arange(100, 100 + bs, dtype=np.uint32)])
+    for t, n in ((A, 3), (Bq, 2)):
+        rc, ids = M.mp_alloc(ug.h, n)
+        assert rc == 0 and ids.tolist() == uo.alloc(n)[1].tolist()
+        assert M.mp_insert(ug.h, t, ids) == uo.insert(t, ids)
+        assert M.mp_free(ug.h, ids) == uo.free(ids) == 0
+    for k in (1, 2, 3):
+        assert M.mp_swap_out(ug.h, lg.h, k, fl) == O.swap_out(uo, lo, k), M.mp_last_error(ug.h)
+        _same_state(uo, ug)
+        _same_state(lo, lg)
+    for t in (A, Bq):
+        assert M.mp_match(lg.h, t, 3)[1].tolist() == lo.match(t)[1].tolist()
+        assert M.mp_match(ug.h, t, 3)[1].tolist() == uo.match(t)[1].tolist() == []
+    low_ids = lo.match(A)[1]
+    assert M.mp_match(lg.h, A, 3)[1].tolist() == low_ids.tolist() and len(low_ids) == 3
+    rc, up = M.mp_swap_in(lg.h, ug.h, low_ids[[0, 2]], fl)                # shallow id first, deep one second
+    rco, up_o = O.swap_in(lo, uo, low_ids[[0, 2]])
+    assert rc == rco == 0 and up.tolist() == up_o.tolist(), M.mp_last_error(lg.h)
+    _same_state(uo, ug)
+    _same_state(lo, lg)
+    assert M.mp_match(ug.h, A, 3)[1].tolist() == uo.match(A)[1].tolist() and len(uo.match(A)[1]) == 3
+    assert M.mp_evict(ug.h, 8) == uo.evict(8) == (0, 0)                   # the deep block is referenced
+    assert M.mp_free(ug.h, up) == uo.free(up) == 0
+    assert M.mp_evict(ug.h, 8) == uo.evict(8) == (0, 3)
+    ug.close()
+    lg.close()
+
+
+@pytest.mark.parametrize("seed,lower_tier,direct,probe", [(0, 1, 0, 0), (1, 1, 1, 0), (2, 0, 0, 0),
+                                                         (3, 1, 0, 1), (4, 0, 1, 1), (5, 1, 0, 0)])
+def test_swap_random_against_oracle(gpu, seed, lower_tier, direct, probe):
+    """Random mix of insert / free / swap_out / swap_in / evict / match on a tight upper pool and
+    a lower pool that sometimes has to evict too: ids, statistics and every byte of both pools."""
+    M, TorchPool = gpu
+    geom = GEOMS["f64"]
+    bs = geom[3]
+    fl = M.MP_DIRECT if direct else 0
+    rng = np.random.default_rng(700 + seed)
+    uo, ug = make_pair(gpu, geom, 20, seed, staging_blocks=3, hash_seed=seed)
+    NB_low = 12 if seed % 2 else 28                     # the small one must evict on demand itself
+    lo, lg = make_pair(gpu, geom, NB_low, seed + 30, staging_blocks=0 if lower_tier else 2,
+                        tier=lower_tier, hash_seed=seed)
+    assert M.mp_set_tunable(ug.h, "device_probe", probe) == 0
+    prompts, held = [], []
+    n_out = n_in = 0
+    for step in range(160):
+        op = int(rng.choice([0, 0, 0, 2, 2, 3, 3, 3, 4, 4, 4, 5, 6]))
+        if op == 0:                                                        # a request finishes prefill
+            if prompts and rng.integers(0, 2):
+                base = prompts[int(rng.integers(0, len(prompts)))]
+                t = np.concatenate([base[: bs * int(rng.integers(0, len(base) // bs + 1))],
+                                    rng.integers(0, 6, int(rng.integers(1, 3 * bs)), dtype=np.uint32)])
+            else:
+                t = rng.integers(0, 6, int(rng.integers(0, 5 * bs)), dtype=np.uint32)
+            nb = len(t) // bs
+            rc, ids = M.mp_alloc(ug.h, nb)
+            rco, ids_o = uo.alloc(nb)
+            assert rc == rco
+            if rc == 0:
+                assert ids.tolist() == ids_o.tolist()
+                assert M.mp_insert(ug.h, t, ids) == uo.insert(t, ids)
+                prompts.append(t)
+                held.append(ids)
+        elif op == 2 and held:
+            ids = held.pop(int(rng.integers(0, len(held))))
+            assert M.mp_free(ug.h, ids) == uo.free(ids) == 0
+        elif op == 3:
+            k = int(rng.integers(0, 7))
+            got = M.mp_swap_out(ug.h, lg.h, k, fl)
+            assert got == O.swap_out(uo, lo, k), (step, M.mp_last_error(ug.h))
+            n_out += got[1]
+        elif op == 4 and prompts:
+            t = prompts[int(rng.integers(0, len(prompts)))]
+            rc, low_ids = M.mp_match(lg.h, t, len(t) // bs)
+            assert low_ids.tolist() == lo.match(t)[1].tolist()
+            if len(low_ids):
+                pick = low_ids[rng.permutation(len(low_ids))[: int(rng.integers(1, len(low_ids) + 1))]]
+                rc, up = M.mp_swap_in(lg.h, ug.h, pick, fl)
+                rco, up_o = O.swap_in(lo, uo, pick)
+                assert rc == rco, (step, rc, rco, M.mp_last_error(lg.h))
+                if rc == 0:
+                    assert up.tolist() == up_o.tolist()
+                    held.append(up)
+                    n_in += len(up)
+        elif op == 5:
+            k = int(rng.integers(0, 3))
+            pg, po = (ug, uo) if rng.integers(0, 4) else (lg, lo)
+            assert M.mp_evict(pg.h, k) == po.evict(k)
+        elif op == 6 and prompts:
+            t = prompts[int(rng.integers(0, len(prompts)))]
+            for pg, po in ((ug, uo), (lg, lo)):
+                assert M.mp_match(pg.h, t, len(t) // bs)[1].tolist() == po.match(t)[1].tolist()
+        _same_state(uo, ug)
+        _same_state(lo, lg)
+    assert n_out >= 10 and n_in >= 3                   # the run did move blocks both ways
+    ug.close()
+    lg.close()

@@ -130,3 +130,24 @@ def test_random_sequences_match_the_oracle(seed):
     assert M.mp_pool_stats(p.g)[1]["n_free"] == NB
     # and the free lists are in the same order
     assert M.mp_alloc(p.g, NB)[1].tolist() == p.o.alloc(NB)[1].tolist()
+
+
+def test_swap_argument_checks_need_no_device():
+    a, b = Pair(8), Pair(8)
+    assert M.mp_swap_out(a.g, a.g, 1)[0] == M.MP_EINVAL                 # one pool is not two tiers
+    assert M.mp_swap_out(a.g, None, 1)[0] == M.MP_EINVAL
+    assert M.mp_swap_out(a.g, b.g, 4) == (0, 0)                         # nothing cached: nothing to move
+    seeded = Pair(8, seed=5)
+    assert M.mp_swap_out(a.g, seeded.g, 1)[0] == M.MP_EINVAL            # tiers of one instance share the seed
+    buf = np.zeros(64, np.uint8)
+    base = (buf.ctypes.data + 15) // 16 * 16
+    rc, other = M.mp_pool_create(3, 1, 8, BS, 2, 8, base)
+    assert rc == 0 and M.mp_swap_out(a.g, other, 1)[0] == M.MP_ESHAPE
+    rc, h1 = M.mp_pool_create(*GEOM, 8, base, tier=M.MP_TIER_HOST_PINNED)
+    rc, h2 = M.mp_pool_create(*GEOM, 8, base, tier=M.MP_TIER_HOST_PINNED)
+    assert M.mp_swap_out(h1, h2, 1)[0] == M.MP_ESHAPE                   # host to host
+    assert M.mp_swap_in(h1, a.g, [0])[0] == M.MP_EINVAL                 # block 0 of h1 is not indexed
+    assert M.mp_swap_in(h1, a.g, [9])[0] == M.MP_EINVAL
+    assert M.mp_swap_in(h1, a.g, [])[0] == 0
+    for h in (other, h1, h2):
+        M.mp_pool_destroy(h)
