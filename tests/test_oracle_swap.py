@@ -53,6 +53,12 @@ def test_script():
     assert up.free(got) == 0
     assert up.evict(10) == (0, 2)
     assert low.match(Bq)[1].tolist() == [0, 3]          # the lower tier keeps its copy
+    # order inside one call: the deepest prefix goes first whatever the list order, so A's chain
+    # is brought up (and stamped) before B's leaf and is the older of the two afterwards
+    rc, got = O.swap_in(low, up, [3, 2])                # b1 (depth 2) listed before a2 (depth 3)
+    assert rc == 0 and up.free(got) == 0
+    assert up.evict(1) == (0, 1)
+    assert len(up.match(A)[1]) == 2 and len(up.match(Bq)[1]) == 2
 
 
 def test_errors_and_limits():
@@ -185,3 +191,45 @@ def test_nothing_cached_is_lost_and_bytes_are_unchanged():
                 else:
                     assert rc == O.ENOMEM
             check_all()
+
+
+def test_lower_tier_evicts_and_is_touched_and_failed_swap_in_lets_go():
+    X, Y, Z = (np.full(BS, v, np.uint32) for v in (1, 2, 3))
+    Q = np.arange(50, 50 + 2 * BS, dtype=np.uint32)
+
+    def cache(p, t):
+        _, ids = p.alloc(len(t) // BS)
+        assert p.insert(t, ids)[0] == 0 and p.free(ids) == 0
+
+    # a lower tier that is full of historical blocks makes room by its own eviction rule
+    up, low = pool(8, 11), pool(3, 12, tier=O.TIER_HOST)
+    for t in (X, Y, Z):
+        cache(low, t)                       # low: three one-block prompts, X oldest
+    cache(up, Q)
+    assert O.swap_out(up, low, 2) == (0, 2)
+    assert [len(low.match(t)[1]) for t in (X, Y, Z, Q)] == [0, 0, 1, 2]
+    assert up.stats()["n_indexed"] == 0
+
+    # swap_in counts as a use of the prefix in the lower tier
+    up, low = pool(8, 13), pool(4, 14, tier=O.TIER_HOST)
+    cache(low, X)
+    cache(low, Y)                           # Y is the more recent one ...
+    rc, got = O.swap_in(low, up, low.match(X)[1])   # (the match itself already touches X)
+    assert rc == 0 and up.free(got) == 0
+    low.match(Y)
+    rc, got = O.swap_in(low, up, [0])       # ... until X (lower block 0) is swapped in again
+    assert rc == 0 and up.free(got) == 0
+    assert low.evict(1) == (0, 1)
+    assert len(low.match(Y)[1]) == 0 and len(low.match(X)[1]) == 1
+
+    # the second prefix cannot be placed: the reference taken for the first is dropped again
+    up, low = pool(3, 15), pool(4, 16, tier=O.TIER_HOST)
+    cache(low, X)
+    cache(low, Y)
+    _, hold = up.alloc(2)                   # one block left above
+    ids = [int(low.match(X)[1][0]), int(low.match(Y)[1][0])]
+    rc, _ = O.swap_in(low, up, ids)
+    assert rc == O.ENOMEM
+    st = up.stats()
+    assert st["n_held"] == 2 and st["n_historical"] == 1      # X stays cached above, unreferenced
+    assert up.evict(1) == (0, 1)
