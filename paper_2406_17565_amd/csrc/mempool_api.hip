@@ -831,6 +831,12 @@ int cache_prefix(TierMove &mv, int32_t leaf, bool keep_last, int32_t *last_out) 
       mv.dst.push_back(mv.fresh[i]);
     }
   if (last_out) *last_out = d ? mv.ids[d - 1] : kNoBlock;
+  // start moving bytes while the host goes on planning: send the queue once it holds 64 MiB
+  // (staged path: a whole staging buffer, so that each call still pipelines its rounds)
+  const mp_pool *x = mv.from->desc.tier == MP_TIER_HBM ? mv.from : mv.to;
+  const uint64_t enough =
+      (mv.flags & MP_DIRECT) ? (64ull << 20) : std::max<uint64_t>(64ull << 20, x->desc.staging_bytes);
+  if ((uint64_t)mv.src.size() * mv.to->B >= enough) return flush_moves(mv);
   return MP_OK;
 }
 
