@@ -64,3 +64,73 @@ class TorchPool:
 
     def stats(self):
         return M.mp_pool_stats(self.h)[1]
+
+
+class MemPoolError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"{M.mp_strerror(code)} ({code}): {text}")
+        self.code = code
+
+
+class MemPool(TorchPool):
+    """The calls of the paper's Table 1 under their own names, on one pool handle.  Argument
+    marshalling only: every method is one call of the C ABI; a negative return code becomes a
+    MemPoolError.  Block lists are numpy int32 arrays."""
+
+    def _ok(self, rc, who=None):
+        if rc != M.MP_OK:
+            raise MemPoolError(rc, M.mp_last_error((who or self).h))
+
+    def alloc_mem(self, n, evict_on_demand=False):
+        rc, ids = M.mp_alloc(self.h, n, M.MP_EVICT_ON_DEMAND if evict_on_demand else 0)
+        self._ok(rc)
+        return ids
+
+    def free_mem(self, blocks):
+        self._ok(M.mp_free(self.h, blocks))
+
+    def insert(self, tokens, blocks):
+        rc, n_new = M.mp_insert(self.h, tokens, blocks)
+        self._ok(rc)
+        return n_new
+
+    def match(self, tokens, pin=False):
+        rc, ids = M.mp_match(self.h, tokens, len(tokens) // self.bs, M.MP_MATCH_PIN if pin else 0)
+        self._ok(rc)
+        return ids
+
+    def delete(self, tokens):
+        rc, n = M.mp_delete(self.h, tokens)
+        self._ok(rc)
+        return n
+
+    def evict(self, n):
+        rc, done = M.mp_evict(self.h, n)
+        self._ok(rc)
+        return done
+
+    def swap_out(self, lower, num_blocks, flags=0):
+        rc, n = M.mp_swap_out(self.h, lower.h, num_blocks, flags)
+        self._ok(rc)
+        return n
+
+    def swap_in(self, lower, lower_blocks, flags=0):
+        rc, ids = M.mp_swap_in(lower.h, self.h, lower_blocks, flags)
+        self._ok(rc, lower)
+        return ids
+
+    def transfer(self, dst, src_blocks, dst_blocks=None, flags=0, private=b""):
+        if dst_blocks is not None:
+            flags |= M.MP_DST_GIVEN
+        rc, ids = M.mp_transfer(self.h, dst.h, src_blocks, dst_blocks, flags, private)
+        self._ok(rc)
+        return ids
+
+    def transfer_with_insert(self, dst, tokens, src_blocks, first_block=0, dst_blocks=None, flags=0,
+                             private=b""):
+        if dst_blocks is not None:
+            flags |= M.MP_DST_GIVEN
+        rc, ids = M.mp_transfer_with_insert(self.h, dst.h, tokens, first_block, src_blocks, dst_blocks,
+                                            flags, private)
+        self._ok(rc)
+        return ids

@@ -808,3 +808,51 @@ def test_swap_random_against_oracle(gpu, seed, lower_tier, direct, probe):
     assert n_out >= 10 and n_in >= 3                   # the run did move blocks both ways
     ug.close()
     lg.close()
+
+
+def test_table1_names_walkthrough(gpu):
+    """Every call of the paper's Table 1 once, through the class that carries their names."""
+    M, TorchPool = gpu
+    from paper_2406_17565_amd.pool import MemPool, MemPoolError
+    geom = GEOMS["tiny"]
+    bs = geom[3]
+    rng = np.random.default_rng(11)
+
+    def pair(NB, seed, **kw):
+        L, H, D, b, e = geom
+        data = W.kv_bytes(np.random.default_rng(seed), 2 * L * NB * b * H * D * e)
+        tier = kw.get("tier", 0)
+        g = MemPool(*geom, NB, **kw)
+        g.load(data)
+        return O.OraclePool(*geom, NB, tier=tier, data=data.copy()), g
+
+    po, p = pair(16, 1, staging_blocks=4)                  # "prefill" instance
+    do, d = pair(12, 2, staging_blocks=4)                  # "decode" instance, HBM
+    ho, h = pair(12, 3, tier=M.MP_TIER_HOST_PINNED)        # its DRAM tier
+    t = rng.integers(0, 32000, 5 * bs + 3, dtype=np.uint32)
+    src = p.alloc_mem(6)
+    assert src.tolist() == po.alloc(6)[1].tolist()
+    assert p.insert(t, src) == po.insert(t, src)[1] == 5
+    got = p.transfer_with_insert(d, t, src, private=b"request 7")
+    assert got.tolist() == O.transfer_with_insert(po, do, t, 0, src)[1].tolist()
+    assert d.match(t).tolist() == do.match(t)[1].tolist() == got[:5].tolist()
+    d.free_mem(got)
+    do.free(got)
+    assert d.swap_out(h, 3) == O.swap_out(do, ho, 3)[1] == 3
+    low = h.match(t)
+    assert low.tolist() == ho.match(t)[1].tolist() and len(low) == 5
+    up = d.swap_in(h, low[-1:])
+    assert up.tolist() == O.swap_in(ho, do, low[-1:])[1].tolist()
+    d.free_mem(up)
+    do.free(up)
+    moved = p.transfer(d, src[:2])
+    assert moved.tolist() == O.transfer(po, do, src[:2])[1].tolist()
+    assert d.delete(t) == do.delete(t)[1]
+    assert d.evict(2) == do.evict(2)[1]
+    for o, g in ((po, p), (do, d), (ho, h)):
+        _same_state(o, g)
+    with pytest.raises(MemPoolError) as e:
+        d.alloc_mem(13)
+    assert e.value.code == M.MP_ENOMEM
+    for g in (p, d, h):
+        g.close()
