@@ -563,40 +563,52 @@ int check_tier_pair(const orc_pool *a, const orc_pool *b) {
 }
 
 // Cache the prefix (tokens, held in `from` under `blocks`) in `to`: transfer_with_insert of the
-// part `to` lacks, new blocks released at once.
+// part `to` lacks, new blocks released at once.  `known` remembers, for the rest of the call,
+// which block of `to` caches each block of that prefix.
 int cache_prefix(orc_pool *from, orc_pool *to, const std::vector<uint32_t> &tokens,
-                 const std::vector<int32_t> &blocks) {
+                 const std::vector<int32_t> &blocks, std::map<int32_t, int32_t> *known) {
   const uint32_t d = (uint32_t)blocks.size();
   const uint32_t m = (uint32_t)walk(to, tokens.data(), d).size();
   std::vector<int32_t> fresh(d - m + 1);
   int rc = orc_transfer_with_insert(from, to, tokens.data(), d * to->bs, m, blocks.data() + m,
                                     fresh.data(), d - m, ORC_EVICT_ON_DEMAND);
   if (rc != ORC_OK) return rc;
-  return orc_free(to, fresh.data(), d - m);
+  rc = orc_free(to, fresh.data(), d - m);
+  std::vector<Node *> there = walk(to, tokens.data(), d);
+  for (uint32_t i = 0; i < d; ++i) (*known)[blocks[i]] = there[i]->block;
+  return rc;
 }
 }  // namespace
 
+// swap_out: the victims evict would take, in that order.  A victim whose prefix this call has
+// not yet cached below is cached there first (one transfer_with_insert of the missing part);
+// a victim lying on a prefix handled earlier in the same call needs nothing below.
 int orc_swap_out(orc_pool_t *upper, orc_pool_t *lower, uint32_t num_blocks, uint32_t *n_swapped) {
   int rc = check_tier_pair(upper, lower);
   if (rc != ORC_OK) return rc;
   if (!n_swapped) return ORC_EINVAL;
+  std::map<int32_t, int32_t> known;  // upper block -> lower block caching the same prefix block
   uint32_t done = 0;
   while (done < num_blocks) {
     Node *victim = next_victim(upper);
     if (!victim) break;
-    std::vector<uint32_t> tokens;
-    std::vector<int32_t> blocks;
-    prefix_of(victim, &tokens, &blocks);
-    rc = cache_prefix(upper, lower, tokens, blocks);
-    if (rc == ORC_ENOMEM) break;  // the lower tier is full of referenced data
-    if (rc != ORC_OK) return rc;
-    evict_one(upper);             // nothing in `upper` changed meanwhile: removes `victim`
+    if (!known.count(victim->block)) {
+      std::vector<uint32_t> tokens;
+      std::vector<int32_t> blocks;
+      prefix_of(victim, &tokens, &blocks);
+      rc = cache_prefix(upper, lower, tokens, blocks, &known);
+      if (rc == ORC_ENOMEM) break;  // the lower tier is full of referenced data
+      if (rc != ORC_OK) return rc;
+    }
+    evict_one(upper);  // nothing in `upper` changed meanwhile: removes `victim`
     ++done;
   }
   *n_swapped = done;
   return ORC_OK;
 }
 
+// swap_in: the call is one use of the lower tier (one clock tick).  Deepest prefix first; a
+// listed block on a prefix handled earlier in the same call only gets its reference.
 int orc_swap_in(orc_pool_t *lower, orc_pool_t *upper, const int32_t *lower_blocks, uint32_t n,
                 int32_t *upper_blocks) {
   int rc = check_tier_pair(lower, upper);
@@ -609,24 +621,29 @@ int orc_swap_in(orc_pool_t *lower, orc_pool_t *upper, const int32_t *lower_block
     for (const Node *a = lower->node_of[lower_blocks[i]]; a->block >= 0; a = a->parent) ++depth;
     order.push_back({depth, i});
   }
+  if (n == 0) return ORC_OK;
   std::stable_sort(order.begin(), order.end(),
                    [](const std::pair<uint32_t, uint32_t> &a, const std::pair<uint32_t, uint32_t> &b) {
                      return a.first > b.first;
                    });
+  ++lower->clock;
+  std::map<int32_t, int32_t> known;  // lower block -> upper block caching the same prefix block
   std::vector<int32_t> taken;
   for (const auto &o : order) {
-    Node *node = lower->node_of[lower_blocks[o.second]];
-    std::vector<uint32_t> tokens;
-    std::vector<int32_t> blocks;
-    prefix_of(node, &tokens, &blocks);
-    ++lower->clock;  // the prefix is used in the lower tier
-    for (Node *a = node; a->block >= 0; a = a->parent) a->last_use = lower->clock;
-    rc = cache_prefix(lower, upper, tokens, blocks);
-    if (rc != ORC_OK) {
-      orc_free(upper, taken.data(), (uint32_t)taken.size());
-      return rc;
+    const int32_t b = lower_blocks[o.second];
+    if (!known.count(b)) {
+      Node *node = lower->node_of[b];
+      std::vector<uint32_t> tokens;
+      std::vector<int32_t> blocks;
+      prefix_of(node, &tokens, &blocks);
+      for (Node *a = node; a->block >= 0; a = a->parent) a->last_use = lower->clock;
+      rc = cache_prefix(lower, upper, tokens, blocks, &known);
+      if (rc != ORC_OK) {
+        orc_free(upper, taken.data(), (uint32_t)taken.size());
+        return rc;
+      }
     }
-    const int32_t up = walk(upper, tokens.data(), (uint32_t)blocks.size()).back()->block;
+    const int32_t up = known[b];
     ++upper->ref[up];
     taken.push_back(up);
     upper_blocks[o.second] = up;

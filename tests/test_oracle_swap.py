@@ -233,3 +233,23 @@ def test_lower_tier_evicts_and_is_touched_and_failed_swap_in_lets_go():
     st = up.stats()
     assert st["n_held"] == 2 and st["n_historical"] == 1      # X stays cached above, unreferenced
     assert up.evict(1) == (0, 1)
+
+
+def test_one_prefix_is_handled_once_per_call():
+    """A chain that goes down (or comes up) within one call costs one index operation in the
+    other tier: later victims / listed blocks on the same prefix only leave (or get a reference)."""
+    up, low = pool(8, 21), pool(8, 22, tier=O.TIER_HOST)
+    t = np.arange(3 * BS, dtype=np.uint32)
+    _, ids = up.alloc(3)
+    up.insert(t, ids)
+    up.free(ids)
+    assert O.swap_out(up, low, 3) == (0, 3)
+    assert low.stats()["clock"] == 1 and low.stats()["n_indexed"] == 3
+    assert up.stats()["n_indexed"] == 0 and up.stats()["n_free"] == 8
+    c_up = up.stats()["clock"]
+    low_ids = low.match(t)[1]                                 # low clock 2
+    rc, got = O.swap_in(low, up, low_ids)                     # whole path listed, root first
+    assert rc == 0 and low.stats()["clock"] == 3 and up.stats()["clock"] == c_up + 1
+    assert up.match(t)[1].tolist() == got.tolist()            # entry i = the upper block of depth i
+    assert up.stats()["n_held"] == 3                          # one reference per listed block
+    assert up.free(got) == 0 and up.evict(3) == (0, 3)
