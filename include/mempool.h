@@ -215,8 +215,9 @@ int mp_transfer_with_insert_batch(mp_pool_t *src, mp_pool_t *dst, const uint32_t
  * used unreferenced leaf); make sure its whole prompt prefix is cached in `lower` -- the part
  * `lower` lacks is copied there and indexed exactly as by mp_transfer_with_insert(upper ->
  * lower, that prefix, MP_EVICT_ON_DEMAND) followed by mp_free of the new lower blocks, so they
- * are historical at once; ancestors that stay cached in `upper` are then cached in both --;
- * then drop the block from upper's index and free it.  Cached data is never lost: whatever
+ * are historical at once; ancestors that stay cached in `upper` are then cached in both; a
+ * victim that lies on a prefix handled earlier in the same call needs nothing below --; then
+ * drop the block from upper's index and free it.  Cached data is never lost: whatever
  * matched in `upper` before still matches in `upper` or `lower` afterwards, unless `lower`
  * itself had to evict.  Stops early, without error, when `upper` has no victim left or `lower`
  * cannot supply blocks; *n_swapped_out = blocks freed in `upper` (their ids are pushed on the
@@ -228,12 +229,14 @@ int mp_swap_out(mp_pool_t *upper, mp_pool_t *lower, uint32_t num_blocks, uint32_
 
 /* swap_in (Table 1: "swap blocks with given address from DRAM to HBM"; section 8.3: historical
  * KV that sits in DRAM is swapped into HBM before prefill uses it).  lower_blocks: n ids that
- * are indexed in `lower` (what mp_match(lower) returned).  For every id, deepest prefix first
- * (ties: list order): the prefix counts as used in `lower` (one clock tick, path touched); the
- * part of it that `upper` lacks is copied up and indexed as by mp_transfer_with_insert(lower ->
- * upper, that prefix, MP_EVICT_ON_DEMAND) followed by mp_free of the new blocks; then
- * upper_blocks_out[i] = the block of `upper` that now caches the same prefix block, with ONE
- * reference taken for the caller (release with mp_free).  `lower` keeps its copy.  On MP_ENOMEM
+ * are indexed in `lower` (what mp_match(lower) returned).  The call is one use of the lower
+ * tier (one clock tick).  For every id, deepest prefix first (ties: list order): unless the id
+ * lies on a prefix handled earlier in the same call, its path is touched in `lower` and the
+ * part of the prefix that `upper` lacks is copied up and indexed as by
+ * mp_transfer_with_insert(lower -> upper, that prefix, MP_EVICT_ON_DEMAND) followed by mp_free
+ * of the new blocks; then upper_blocks_out[i] = the block of `upper` that caches the same prefix
+ * block, with ONE reference taken for the caller (release with mp_free).  Listing a whole
+ * matched path therefore costs one copy and one index operation.  `lower` keeps its copy.  On MP_ENOMEM
  * (upper cannot supply blocks) the references taken so far are dropped again; blocks already
  * brought up stay cached. */
 int mp_swap_in(mp_pool_t *lower, mp_pool_t *upper, const int32_t *lower_blocks, uint32_t n,

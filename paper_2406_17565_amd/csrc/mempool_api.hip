@@ -763,9 +763,13 @@ int twi_core(mp_pool *src, mp_pool *dst, const uint32_t *tokens, const uint32_t 
 // Both directions cache a prompt prefix that one pool holds in the other pool.  The index work
 // is done call by call in the defined order; the copies are collected and share launches.
 struct TierMove {
-  TierMove(mp_pool *f, mp_pool *t, uint32_t fl) : from(f), to(t), flags(fl) {}
+  TierMove(mp_pool *f, mp_pool *t, uint32_t fl)
+      : from(f), to(t), flags(fl), known(f->desc.n_blocks, kNoBlock) {}
   mp_pool *from, *to;
   uint32_t flags;
+  // for the rest of the call: block of `to` that caches the same prefix block as block b of
+  // `from` (set for every block on a prefix that has been handled)
+  std::vector<int32_t> known;
   std::vector<int32_t> src, dst;  // pending copies: block src[i] of `from` -> block dst[i] of `to`
   std::vector<uint32_t> tokens;
   std::vector<uint64_t> hashes;
@@ -830,6 +834,8 @@ int cache_prefix(TierMove &mv, int32_t leaf, bool keep_last, int32_t *last_out) 
       mv.src.push_back(mv.path[m + i]);
       mv.dst.push_back(mv.fresh[i]);
     }
+  for (uint32_t i = 0; i < d; ++i)
+    if (ti.indexed(mv.ids[i]) || (keep_last && i + 1 == d)) mv.known[mv.path[i]] = mv.ids[i];
   if (last_out) *last_out = d ? mv.ids[d - 1] : kNoBlock;
   // start moving bytes while the host goes on planning: send the queue once it holds 64 MiB
   // (staged path: a whole staging buffer, so that each call still pipelines its rounds)
@@ -1267,12 +1273,14 @@ int mp_swap_out(mp_pool_t *upper, mp_pool_t *lower, uint32_t num_blocks, uint32_
     while (freed.size() < num_blocks) {
       const int32_t victim = upper->idx.next_victim();
       if (victim == kNoBlock) break;
-      rc = cache_prefix(mv, victim, false, nullptr);
-      if (rc == MP_ENOMEM) {  // the lower tier is full of referenced data: not an error
-        rc = MP_OK;
-        break;
+      if (mv.known[victim] == kNoBlock) {  // else: on a prefix this call has already cached below
+        rc = cache_prefix(mv, victim, false, nullptr);
+        if (rc == MP_ENOMEM) {  // the lower tier is full of referenced data: not an error
+          rc = MP_OK;
+          break;
+        }
+        if (rc != MP_OK) break;
       }
-      if (rc != MP_OK) break;
       freed.push_back(upper->idx.evict_next_held());
     }
     if (rc == MP_OK) rc = flush_moves(mv);
@@ -1308,14 +1316,18 @@ int mp_swap_in(mp_pool_t *lower, mp_pool_t *upper, const int32_t *lower_blocks, 
                        return a.first > b.first;
                      });
     std::vector<int32_t> taken;
+    lower->idx.tick();  // the call is one use of the lower tier
     for (const auto &o : order) {
       const int32_t b = lower_blocks[o.second];
-      lower->idx.path_to(b, mv.path);
-      lower->idx.tick();  // the prefix is used in the lower tier
-      lower->idx.touch(mv.path.data(), (uint32_t)mv.path.size());
-      int32_t up = kNoBlock;
-      rc = cache_prefix(mv, b, true, &up);
-      if (rc != MP_OK) break;
+      int32_t up = mv.known[b];
+      if (up != kNoBlock) {  // on a prefix brought up earlier in this call: only the reference
+        upper->idx.pin(up);
+      } else {
+        lower->idx.path_to(b, mv.path);
+        lower->idx.touch(mv.path.data(), (uint32_t)mv.path.size());
+        rc = cache_prefix(mv, b, true, &up);
+        if (rc != MP_OK) break;
+      }
       taken.push_back(up);
       upper_blocks_out[o.second] = up;
     }
