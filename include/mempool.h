@@ -283,7 +283,9 @@ int mp_profile_read(mp_pool_t *p, int kind, double *total_ms_out, uint64_t *laun
 
 /* Kernel launch-shape knobs (for tuning sweeps; defaults are chosen per geometry, and the
  * value -1 restores the default).
- * key: "order" (0 record-major, 1 plane-major), "unroll" (1,2,4,8), "wg_per_cu" (0 = one
+ * key: "order" (0 record-major, 1 plane-major), "plane_tile" (>0: that many planes of an
+ * entry are walked together, rounded down to a divisor of the plane count -- all planes is
+ * order 0, one plane is order 1; 0 = what "order" says), "unroll" (1,2,4,8), "wg_per_cu" (0 = one
  * workgroup per tile group, >0 = persistent grid of that many workgroups per CU),
  * "nontemporal" (0/1), "waves_per_wg" (1 or 4), "xcd_contiguous" (0/1: each XCD walks one
  * contiguous eighth of the work instead of every eighth workgroup), "item_limit" (>0: cap on

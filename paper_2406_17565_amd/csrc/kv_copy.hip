@@ -30,6 +30,7 @@ FastDiv make_fastdiv(uint32_t d) {
 CopyTune default_tune(CopyTune t, uint64_t frag_bytes, bool both_sides_discrete_pools,
                       bool dst_is_discrete_pool) {
   if (t.order < 0) t.order = both_sides_discrete_pools ? 1 : 0;
+  if (t.plane_tile < 0) t.plane_tile = 0;  // 0: what `order` says
   if (t.unroll < 0) t.unroll = 1;
   if (t.wg_per_cu < 0) t.wg_per_cu = 0;
   if (t.nontemporal < 0) t.nontemporal = 1;
@@ -53,10 +54,13 @@ struct CopyArgs {
   uint32_t frag_vecs;  // F / 16
   uint32_t n_planes;
   uint32_t n_entries;
-  uint32_t order;      // 0: entry-major walk, 1: plane-major walk
   uint32_t xcd_span;   // workgroups per XCD for the contiguous re-mapping, 0 = off
+  // The walk: plane tiles outermost, then entries, then the planes of the tile, then the
+  // chunks of a fragment.  A tile of all planes walks records (entry-major), a tile of one
+  // plane walks planes (plane-major).
   FastDiv by_chunks;   // / chunks_per_frag
-  FastDiv by_inner;    // / n_planes (order 0) or / n_entries (order 1)
+  FastDiv by_tile;     // / planes per tile (divides n_planes)
+  FastDiv by_entries;  // / n_entries
 };
 
 // The tables are separate restrict-qualified read-only arguments so that the wave-uniform
@@ -74,13 +78,14 @@ __global__ __launch_bounds__(64 * W) void kv_block_copy(const CopyArgs a,
   uint32_t wg = blockIdx.x;
   if (a.xcd_span && wg < 8u * a.xcd_span) wg = (wg & 7u) * a.xcd_span + (wg >> 3);
   for (uint32_t item = wg * W + wave; item < a.n_items; item += step) {
-    // wave-uniform decomposition: item = (outer * inner_count + inner) * chunks + c
+    // wave-uniform decomposition: item = ((tile * n_entries + i) * tile_planes + p_in) * chunks + c
     const uint32_t q = fastdiv(item, a.by_chunks);
     const uint32_t c = item - q * a.by_chunks.d;
-    const uint32_t o = fastdiv(q, a.by_inner);
-    const uint32_t r = q - o * a.by_inner.d;
-    const uint32_t i = a.order == 0 ? o : r;  // table entry
-    const uint32_t p = a.order == 0 ? r : o;  // plane = layer * 2 + (K|V)
+    const uint32_t q2 = fastdiv(q, a.by_tile);
+    const uint32_t p_in = q - q2 * a.by_tile.d;
+    const uint32_t tile = fastdiv(q2, a.by_entries);
+    const uint32_t i = q2 - tile * a.by_entries.d;   // table entry
+    const uint32_t p = tile * a.by_tile.d + p_in;    // plane = layer * 2 + (K|V)
     const uint32_t sid = __builtin_amdgcn_readfirstlane(src_tbl ? (uint32_t)src_tbl[i] : i);
     const uint32_t did = __builtin_amdgcn_readfirstlane(dst_tbl ? (uint32_t)dst_tbl[i] : i);
     const u32x4 *s = reinterpret_cast<const u32x4 *>(a.src_base + p * a.src_plane_stride +
@@ -187,8 +192,11 @@ hipError_t launch_block_copy(const CopySide &src, const CopySide &dst, uint32_t 
     a.n_planes = n_planes;
     a.n_entries = cnt;
     a.by_chunks = make_fastdiv(chunks);
-    a.by_inner = make_fastdiv(tune.order == 0 ? n_planes : cnt);
-    a.order = (uint32_t)tune.order;
+    uint32_t tile_planes = tune.plane_tile > 0 ? std::min<uint32_t>((uint32_t)tune.plane_tile, n_planes)
+                                               : (tune.order == 0 ? n_planes : 1u);
+    while (n_planes % tile_planes) --tile_planes;  // a divisor of the plane count
+    a.by_tile = make_fastdiv(tile_planes);
+    a.by_entries = make_fastdiv(cnt);
     const uint32_t W = tune.waves_per_wg == 1 ? 1u : 4u;
     uint32_t wgs = (a.n_items + W - 1u) / W;
     if (tune.wg_per_cu > 0) {

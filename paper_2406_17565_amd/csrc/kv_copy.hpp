@@ -22,6 +22,8 @@ struct CopySide {
 // Launch shape of the copy kernel.  -1 = choose from the geometry (see default_tune).
 struct CopyTune {
   int order = -1;           // 0: walk records (entry-major), 1: walk planes (plane-major)
+  int plane_tile = -1;      // >0: planes walked together per entry (rounded down to a divisor of
+                            // the plane count); the two orders are its extremes: all planes / 1
   int unroll = -1;          // 16-byte loads in flight per lane: 1, 2, 4 or 8
   int wg_per_cu = -1;       // 0: one pass over the items; >0: persistent grid of that many WGs per CU
   int nontemporal = -1;     // stream past the caches

@@ -1452,6 +1452,7 @@ int mp_set_tunable(mp_pool_t *p, const char *key, int value) {
     const std::string k(key);
     const bool dflt = value == -1;  // -1 restores the geometry-based default
     if (k == "order" && (dflt || value == 0 || value == 1)) p->tune.order = value;
+    else if (k == "plane_tile" && value >= -1 && value <= 65535) p->tune.plane_tile = value;
     else if (k == "unroll" && (dflt || value == 1 || value == 2 || value == 4 || value == 8)) p->tune.unroll = value;
     else if (k == "wg_per_cu" && value >= -1 && value <= 64) p->tune.wg_per_cu = value;
     else if (k == "nontemporal" && (dflt || value == 0 || value == 1)) p->tune.nontemporal = value;

@@ -105,21 +105,23 @@ def test_gather_scatter_all_launch_shapes(gpu, name):
     src_tbl = rng.integers(0, NB, n).astype(np.int32)      # duplicates allowed when reading
     dst_tbl = W.random_table(rng, NB, n)
     want_staging = o.gather(src_tbl)
-    shapes = [(order, u, wg, nt, w, xcd) for order in (0, 1) for u in (1, 2, 4, 8)
+    shapes = [(order, 0, u, wg, nt, w, xcd) for order in (0, 1) for u in (1, 2, 4, 8)
               for wg, nt, w, xcd in ((0, 1, 4, 0), (2, 0, 1, 1), (0, 1, 1, 1), (1, 1, 4, 1))]
-    for order, u, wg, nt, w, xcd in shapes:
-        for k, v in (("order", order), ("unroll", u), ("wg_per_cu", wg), ("nontemporal", nt),
-                     ("waves_per_wg", w), ("xcd_contiguous", xcd)):
+    shapes += [(0, tile, 1, wg, 1, w, xcd) for tile in (2, 3, 4, 5, 64)    # 5 is rounded to a divisor
+               for wg, w, xcd in ((0, 1, 1), (2, 4, 0))]
+    for order, tile, u, wg, nt, w, xcd in shapes:
+        for k, v in (("order", order), ("plane_tile", tile), ("unroll", u), ("wg_per_cu", wg),
+                     ("nontemporal", nt), ("waves_per_wg", w), ("xcd_contiguous", xcd)):
             assert M.mp_set_tunable(g.h, k, v) == 0
         g.staging.zero_()
         assert M.mp_gather(g.h, src_tbl) == 0, M.mp_last_error(g.h)
-        assert np.array_equal(g.staging_bytes(n), want_staging), (name, order, u, wg, nt, w, xcd)
+        assert np.array_equal(g.staging_bytes(n), want_staging), (name, order, tile, u, wg, nt, w, xcd)
         # scatter the gathered records under a permuted table; oracle does the same
         o2 = O.OraclePool(*geom, NB, data=o.data.copy())
         o2.scatter(dst_tbl, want_staging)
         before = g.bytes()
         assert M.mp_scatter(g.h, dst_tbl) == 0
-        assert np.array_equal(g.bytes(), o2.data), (name, order, u, wg, nt, w, xcd)
+        assert np.array_equal(g.bytes(), o2.data), (name, order, tile, u, wg, nt, w, xcd)
         g.load(before)
     assert M.mp_gather(g.h, np.zeros(0, np.int32)) == 0
     assert M.mp_gather(g.h, [NB]) == M.MP_EINVAL
