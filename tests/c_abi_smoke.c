@@ -13,6 +13,8 @@
 extern int hipMalloc(void **p, size_t n);
 extern int hipFree(void *p);
 extern int hipMemcpy(void *d, const void *s, size_t n, int kind);
+extern int hipHostMalloc(void **p, size_t n, unsigned flags);
+extern int hipHostFree(void *p);
 enum { H2D = 1, D2H = 2 };
 
 #define CHECK(x) do { if (!(x)) { fprintf(stderr, "FAILED line %d: %s\n", __LINE__, #x); return 1; } } while (0)
@@ -76,6 +78,33 @@ int main(int argc, char **argv) {
       for (pl = 0; pl < 4; ++pl)
         CHECK(memcmp(h_dst + ((size_t)pl * NB + d_ids[k]) * F,
                      h_src + ((size_t)pl * NB + s_ids[k]) * F, F) == 0);
+    {
+      /* the receiver's two cached blocks move down to a pinned-host tier and one comes back */
+      void *h_low = NULL;
+      mp_pool_t *low = NULL;
+      mp_pool_desc_t dl;
+      uint32_t n_out = 0;
+      int32_t one = 1, up = -1;
+      const unsigned char *rec;
+      CHECK(hipHostMalloc(&h_low, 4 * (size_t)B, 0) == 0);
+      dl = desc(h_low, NULL, 0, 4);
+      dl.tier = MP_TIER_HOST_PINNED;
+      CHECK(mp_pool_create(&dl, &low) == MP_OK);
+      CHECK(mp_free(dst, d_ids, 3) == MP_OK);
+      CHECK(mp_swap_out(dst, low, 2, MP_DIRECT, &n_out) == MP_OK && n_out == 2);
+      CHECK(mp_match(dst, tokens, 10, got, 2, &m, 0) == MP_OK && m == 0);
+      CHECK(mp_match(low, tokens, 10, got, 2, &m, 0) == MP_OK && m == 2 && got[0] == 0 && got[1] == 1);
+      for (k = 0; k < 2; ++k)                                 /* host block = one record [plane][F] */
+        for (pl = 0; pl < 4; ++pl) {
+          rec = (const unsigned char *)h_low + (size_t)k * B + (size_t)pl * F;
+          CHECK(memcmp(rec, h_src + ((size_t)pl * NB + s_ids[k]) * F, F) == 0);
+        }
+      CHECK(mp_swap_in(low, dst, &one, 1, &up, MP_DIRECT) == MP_OK && up >= 0);
+      CHECK(mp_match(dst, tokens, 10, got, 2, &m, 0) == MP_OK && m == 2 && got[1] == up);
+      CHECK(mp_free(dst, &up, 1) == MP_OK);
+      CHECK(mp_pool_destroy(low) == MP_OK);
+      hipHostFree(h_low);
+    }
     CHECK(mp_pool_destroy(src) == MP_OK && mp_pool_destroy(dst) == MP_OK);
     hipFree(d_src); hipFree(d_dst); hipFree(d_stage);
     printf("c_abi_smoke gpu ok\n");
