@@ -374,6 +374,26 @@ def api_latency(args):
         M.mp_insert(p.h, prompt, ids)
         return time.perf_counter() - t0
     out["insert_256_blocks_end_to_end_us"] = round(min(ins() for _ in range(20)) * 1e6, 1)
+    # Prefix check against prompt length (the paper's caching study, section 8.4, finds a
+    # hash-per-block prefix check growing steeply with the prompt; here one chained pass and one
+    # table walk: linear, a few ns per token).  Fully cached prompts, GPU hashing included.
+    M.mp_free(p.h, ids); M.mp_evict(p.h, 4096)
+    by_len = {}
+    for nblk in (64, 256, 1024, 4096):
+        t_a = rng.integers(0, g.vocab, nblk * g.bs, dtype=np.uint32)
+        t_b = t_a.copy()
+        t_b[-1] ^= 1                                  # same prefix but for the last block
+        rc, held = M.mp_alloc(p.h, nblk)
+        assert rc == 0 and M.mp_insert(p.h, t_a, held)[0] == 0
+        alt = [0]
+
+        def one():
+            alt[0] ^= 1
+            return M.mp_match(p.h, t_b if alt[0] else t_a, nblk)
+        by_len[nblk * g.bs] = round(best(one, reps=20) * 1e6, 1)
+        M.mp_free(p.h, held); M.mp_evict(p.h, 4096)
+    out["match_fully_cached_us_by_prompt_tokens"] = by_len
+    rc, ids = M.mp_alloc(p.h, 256)
     turns = build_epoch(W, g, 3, 0)[2:4]          # 64 prompts of about 1.5K / 2K tokens
     turn = turns[1]
     nb = int(((turn["tok_off"][1:] - turn["tok_off"][:-1]) // g.bs).sum())
