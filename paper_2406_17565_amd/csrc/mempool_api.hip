@@ -76,9 +76,14 @@ struct DeviceCtx {
   uint32_t *m_tokens = nullptr;
   MirrorBuf m_updates;  // pinned change records the apply kernel reads
   MirrorBuf m_out;      // pinned: [out offsets][matched counts][block ids]
+  // Ordering of the staging buffer between the main stream and the side stream (host-tier
+  // copies): `staging_idle` is recorded on the main stream when a host-tier transfer starts and
+  // the side stream waits for it, so the copy engine never touches staging before every
+  // earlier main-stream user (gather, scatter, HBM->HBM rounds) is done with it; inside the
+  // call the two slots are handed back and forth with the per-slot events.
+  hipEvent_t staging_idle = nullptr;
   hipEvent_t slot_filled[2] = {nullptr, nullptr};   // main -> side (or side -> main)
   hipEvent_t slot_drained[2] = {nullptr, nullptr};  // the other direction
-  bool slot_busy[2] = {false, false};
   bool profiling = false;
   std::vector<ProfRec> prof;
   double prof_ms[kProfKinds] = {0, 0, 0, 0};
@@ -148,6 +153,8 @@ void destroy_device_objects(DeviceCtx &d) {
     if (d.tables_uploaded[s]) (void)hipEventDestroy(d.tables_uploaded[s]);
     d.tables_uploaded[s] = nullptr;
   }
+  if (d.staging_idle) (void)hipEventDestroy(d.staging_idle);
+  d.staging_idle = nullptr;
   for (int s = 0; s < 2; ++s) {
     if (d.slot_filled[s]) (void)hipEventDestroy(d.slot_filled[s]);
     if (d.slot_drained[s]) (void)hipEventDestroy(d.slot_drained[s]);
@@ -165,6 +172,7 @@ int create_device_objects(mp_pool *p) {
   HIP_TRY(p, hipStreamCreateWithFlags(&d.side, hipStreamNonBlocking));
   for (int s = 0; s < DeviceCtx::kTableSlots; ++s)
     HIP_TRY(p, hipEventCreateWithFlags(&d.tables_uploaded[s], hipEventDisableTiming));
+  HIP_TRY(p, hipEventCreateWithFlags(&d.staging_idle, hipEventDisableTiming));
   for (int s = 0; s < 2; ++s) {
     HIP_TRY(p, hipEventCreateWithFlags(&d.slot_filled[s], hipEventDisableTiming));
     HIP_TRY(p, hipEventCreateWithFlags(&d.slot_drained[s], hipEventDisableTiming));
@@ -574,6 +582,15 @@ int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *
 
   // One end is the pinned-host tier (aggregated layout: a block is one contiguous record).
   // Two staging slots let the kernel of round k+1 overlap the host-link copies of round k.
+  //
+  // Who may touch staging, and when.  Kernels read and write it on the main stream only; the
+  // copy engine reads (HBM -> host) or writes (host -> HBM) it on the side stream only.  The
+  // main stream is the single line of order between calls: a host-tier call starts by making
+  // the side stream wait for everything enqueued on the main stream so far (earlier
+  // asynchronous gathers, scatters and HBM -> HBM rounds may still be using any part of the
+  // buffer, whatever slot layout they had), and it ends with the main stream ordered behind
+  // every side-stream copy it issued.  In between, a slot goes back and forth with one event
+  // per direction, and a slot is reused only after the event of its previous round.
   uint32_t n_slots = 2;
   uint64_t slot_bytes = (x->desc.staging_bytes / 2) / B * B;
   if (slot_bytes == 0 || (uint64_t)n * B <= x->desc.staging_bytes / B * B) {
@@ -583,13 +600,16 @@ int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *
   const uint32_t cap = (uint32_t)std::min<uint64_t>(slot_bytes / B, 0xffffffffu);
   uint8_t *host_base = (uint8_t *)(s_hbm ? dst : src)->desc.base;
   const int32_t *host_ids = s_hbm ? dst_ids : src_ids;
+  HIP_TRY(x, hipEventRecord(d.staging_idle, d.stream));
+  HIP_TRY(x, hipStreamWaitEvent(d.side, d.staging_idle, 0));
+  bool slot_used[2] = {false, false};  // in this call: its `drained` event is pending
   uint32_t round = 0;
   for (uint32_t first = 0; first < n; first += cap, ++round) {
     const uint32_t cnt = std::min(cap, n - first);
     const uint32_t s = round % n_slots;
     uint8_t *slot = staging + (uint64_t)s * slot_bytes;
     if (s_hbm) {  // HBM -> host: gather on the main stream, then device-to-host on the side stream
-      if (d.slot_busy[s]) HIP_TRY(x, hipStreamWaitEvent(d.stream, d.slot_drained[s], 0));
+      if (slot_used[s]) HIP_TRY(x, hipStreamWaitEvent(d.stream, d.slot_drained[s], 0));
       {
         ProfScope ps(x, kProfGather, 2ull * cnt * B);
         HIP_TRY(x, launch_block_copy(pool_side(src, d_src + first), record_side(x, slot, x->P), cnt,
@@ -597,8 +617,8 @@ int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *
       }
       HIP_TRY(x, hipEventRecord(d.slot_filled[s], d.stream));
       HIP_TRY(x, hipStreamWaitEvent(d.side, d.slot_filled[s], 0));
-    } else {  // host -> HBM: wait until the scatter that last used this slot is done
-      if (d.slot_busy[s]) HIP_TRY(x, hipStreamWaitEvent(d.side, d.slot_drained[s], 0));
+    } else {  // host -> HBM: wait until the scatter that last read this slot is done
+      if (slot_used[s]) HIP_TRY(x, hipStreamWaitEvent(d.side, d.slot_drained[s], 0));
     }
     for (uint32_t i = 0; i < cnt;) {  // one copy per run of consecutive host block ids
       uint32_t j = i + 1;
@@ -623,11 +643,11 @@ int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *
       }
       HIP_TRY(x, hipEventRecord(d.slot_drained[s], d.stream));
     }
-    d.slot_busy[s] = true;
+    slot_used[s] = true;
   }
-  if (s_hbm) {  // make the main stream the single point of completion
+  if (s_hbm) {  // the main stream becomes the single point of completion
     for (uint32_t s = 0; s < n_slots; ++s)
-      if (d.slot_busy[s]) HIP_TRY(x, hipStreamWaitEvent(d.stream, d.slot_drained[s], 0));
+      if (slot_used[s]) HIP_TRY(x, hipStreamWaitEvent(d.stream, d.slot_drained[s], 0));
   }
   return MP_OK;
 }

@@ -468,6 +468,71 @@ def test_host_tier_both_directions(gpu):
         p.close()
 
 
+def test_staging_is_ordered_between_main_and_side_stream(gpu):
+    """Asynchronous multi-round transfers OUT of a pool keep its staging buffer busy on the
+    main stream; host-tier transfers INTO the same pool, issued right behind them, fill that
+    buffer on the side stream.  Nothing is synchronised in between, in either slot layout (two
+    half-buffer slots, then one whole-buffer slot), so the result equals the oracle's sequential
+    one only if the side stream waits for every earlier user of the buffer."""
+    M, TorchPool = gpu
+    geom = GEOMS["f32k"]                       # 256 KiB records
+    bs = geom[3]
+    xo, xg = make_pair(gpu, geom, 768, 11, staging_blocks=32)
+    yo, yg = make_pair(gpu, geom, 1100, 12, staging_blocks=0)
+    ho, hg = make_pair(gpu, geom, 256, 13, staging_blocks=0, tier=1)
+    rng = np.random.default_rng(14)
+    rc, held = M.mp_alloc(xg.h, 512)
+    assert rc == 0 and held.tolist() == xo.alloc(512)[1].tolist()
+    # the host tier caches 8 prompts of 16 blocks (historical), plus 96 held blocks
+    prompts = [rng.integers(0, 32000, 16 * bs, dtype=np.uint32) for _ in range(8)]
+    for t in prompts:
+        rc, ids = M.mp_alloc(hg.h, 16)
+        assert rc == 0 and ids.tolist() == ho.alloc(16)[1].tolist()
+        assert M.mp_insert(hg.h, t, ids) == ho.insert(t, ids)
+        assert M.mp_free(hg.h, ids) == ho.free(ids) == 0
+    rc, h_held = M.mp_alloc(hg.h, 96)
+    assert rc == 0 and h_held.tolist() == ho.alloc(96)[1].tolist()
+    low_ids = np.concatenate([ho.match(t)[1] for t in prompts[:3]])
+    for t in prompts[:3]:
+        assert M.mp_match(hg.h, t, 16)[0] == 0
+    fl = M.MP_ASYNC
+    # 1. 16 staging rounds on the main stream, not waited for
+    tbl1 = rng.permutation(held)[:512].astype(np.int32)
+    rc, d1 = M.mp_transfer(xg.h, yg.h, tbl1, flags=fl)
+    assert rc == 0 and d1.tolist() == O.transfer(xo, yo, tbl1)[1].tolist()
+    # 2. host -> X through the same buffer, two slots of 16 records, copies on the side stream
+    src2 = rng.permutation(h_held)[:80].astype(np.int32)
+    rc, d2 = M.mp_transfer(hg.h, xg.h, src2, flags=fl)
+    assert rc == 0 and d2.tolist() == O.transfer(ho, xo, src2)[1].tolist(), M.mp_last_error(hg.h)
+    # 3. out of X again (main stream), then a host -> X transfer that fits ONE whole-buffer slot
+    tbl3 = rng.permutation(held)[:500].astype(np.int32)
+    rc, d3 = M.mp_transfer(xg.h, yg.h, tbl3, flags=fl)
+    assert rc == 0 and d3.tolist() == O.transfer(xo, yo, tbl3)[1].tolist()
+    src4 = rng.permutation(h_held)[:30].astype(np.int32)
+    rc, d4 = M.mp_transfer(hg.h, xg.h, src4, flags=fl)
+    assert rc == 0 and d4.tolist() == O.transfer(ho, xo, src4)[1].tolist()
+    # 4. a gather and a scatter of the data-plane pieces, then swap_in through the same buffer
+    assert M.mp_gather(xg.h, tbl1[:32], fl) == 0
+    assert M.mp_scatter(xg.h, d2[:32], fl) == 0
+    xo.scatter(d2[:32], xo.gather(tbl1[:32]))
+    rc, up = M.mp_swap_in(hg.h, xg.h, low_ids)
+    rco, up_o = O.swap_in(ho, xo, low_ids)
+    assert rc == rco == 0 and up.tolist() == up_o.tolist(), M.mp_last_error(hg.h)
+    # 5. X -> host right behind an asynchronous main-stream user, then host -> X once more
+    rc, d5 = M.mp_transfer(xg.h, yg.h, tbl1[:64], flags=fl)
+    assert rc == 0 and d5.tolist() == O.transfer(xo, yo, tbl1[:64])[1].tolist()
+    rc, d6 = M.mp_transfer(xg.h, hg.h, tbl3[:24], flags=fl)
+    assert rc == 0 and d6.tolist() == O.transfer(xo, ho, tbl3[:24])[1].tolist(), M.mp_last_error(xg.h)
+    rc, d7 = M.mp_transfer(hg.h, xg.h, d6, flags=fl)
+    assert rc == 0 and d7.tolist() == O.transfer(ho, xo, d6)[1].tolist()
+    torch.cuda.synchronize()
+    _same_state(xo, xg)
+    _same_state(yo, yg)
+    _same_state(ho, hg)
+    for p in (xg, yg, hg):
+        p.close()
+
+
 def test_async_and_callback(gpu):
     M, TorchPool = gpu
     geom = GEOMS["f32k"]
