@@ -488,12 +488,8 @@ CopySide record_side(const mp_pool *p, void *base, uint32_t planes) {
   return s;
 }
 
-bool tables_overlap(const mp_pool *p, const int32_t *a, const int32_t *b, uint32_t n) {
-  std::vector<uint8_t> seen(p->desc.n_blocks, 0);
-  for (uint32_t i = 0; i < n; ++i) seen[a[i]] = 1;
-  for (uint32_t i = 0; i < n; ++i)
-    if (seen[b[i]]) return true;
-  return false;
+bool tables_overlap(mp_pool *p, const int32_t *a, const int32_t *b, uint32_t n) {
+  return p->idx.lists_overlap(a, b, n);
 }
 
 // Which staging problems would the copy hit?  Checked before any state changes.
@@ -1391,12 +1387,8 @@ int mp_scatter(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags) {
     if (!p) return MP_EINVAL;
     if (!tbl && n) return fail(p, MP_EINVAL, "null table");
     if (p->desc.tier != MP_TIER_HBM) return fail(p, MP_EINVAL, "mp_scatter needs an HBM pool");
-    std::vector<uint8_t> seen(p->desc.n_blocks, 0);
-    for (uint32_t i = 0; i < n; ++i) {
-      if (!p->idx.in_range(tbl[i]) || seen[tbl[i]])
-        return fail(p, MP_EINVAL, "block id out of range or repeated");
-      seen[tbl[i]] = 1;
-    }
+    if (!p->idx.in_range_and_distinct(tbl, n))
+      return fail(p, MP_EINVAL, "block id out of range or repeated");
     if (n == 0) return MP_OK;
     if (!p->desc.staging || (uint64_t)n * p->B > p->desc.staging_bytes)
       return fail(p, MP_ENOSTAGING, "staging buffer too small for the table");

@@ -248,6 +248,31 @@ class PoolIndex {
     return ok;
   }
 
+  // Does any id of b[0..n) also occur in a[0..n)?  (ids already range-checked)
+  bool lists_overlap(const int32_t *a, const int32_t *b, uint32_t n) {
+    for (uint32_t i = 0; i < n; ++i) mark_[a[i]] = 1;
+    bool hit = false;
+    for (uint32_t i = 0; i < n && !hit; ++i) hit = mark_[b[i]] != 0;
+    for (uint32_t i = 0; i < n; ++i) mark_[a[i]] = 0;
+    return hit;
+  }
+
+  // Are ids in range and pairwise distinct?  (a scatter table; no reference needed)
+  bool in_range_and_distinct(const int32_t *blocks, uint32_t n) {
+    bool ok = true;
+    uint32_t i = 0;
+    for (; i < n; ++i) {
+      int32_t b = blocks[i];
+      if (!in_range(b) || mark_[b]) {
+        ok = false;
+        break;
+      }
+      mark_[b] = 1;
+    }
+    for (uint32_t j = 0; j < i; ++j) mark_[blocks[j]] = 0;
+    return ok;
+  }
+
   // insert proper: one clock tick, existing prefix touched, the rest adopted.  ids[i] is
   // ignored for blocks already present.  Returns the number of nodes created.
   uint32_t insert(const uint32_t *tokens, const uint64_t *hashes, uint32_t nblk,
