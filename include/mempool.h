@@ -242,6 +242,28 @@ int mp_swap_out(mp_pool_t *upper, mp_pool_t *lower, uint32_t num_blocks, uint32_
 int mp_swap_in(mp_pool_t *lower, mp_pool_t *upper, const int32_t *lower_blocks, uint32_t n,
                int32_t *upper_blocks_out, uint32_t flags);
 
+/* For callers that cannot allocate device memory -- code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc: mp_transfer with an explicit destination list between
+ * two HBM pools that allocates nothing.  Where mp_transfer keeps the two block tables in
+ * library-allocated device buffers, this call keeps them in a fixed array inside the library's
+ * device image (2 * MP_STATIC_MAX_BLOCKS ids = 512 KiB on every GPU the library runs on, held
+ * until the process ends); the call makes no hipMalloc / hipFree / hipHostMalloc, creates no
+ * stream or event, and grows no host container.
+ *   src_blocks, dst_blocks: n host ids each; source ids held or historical, destination ids
+ *   held and distinct (as for mp_transfer with MP_DST_GIVEN).  n <= MP_STATIC_MAX_BLOCKS, else
+ *   MP_EINVAL ("more than MP_STATIC_MAX_BLOCKS ..." in mp_last_error).
+ *   flags: MP_DIRECT (one fused kernel) and MP_ASYNC; without MP_DIRECT the records go through
+ *   src's staging buffer in rounds, as in mp_transfer.  Both pools must be HBM pools (MP_ESHAPE).
+ *   The work runs on src's stream; the tables are uploaded on that stream too, so calls on one
+ *   stream may follow each other without waiting.  Pageable host tables are read before the
+ *   call returns; tables in pinned host memory must stay unchanged until the work has run.
+ *   Every call on a GPU shares that GPU's one array: calls that overlap in time on DIFFERENT
+ *   streams of one GPU race on it -- the caller orders them.
+ *   No receiver callback, no kernel timing (both would allocate). */
+#define MP_STATIC_MAX_BLOCKS 65536u
+int mp_transfer_static(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks,
+                       const int32_t *dst_blocks, uint32_t n, uint32_t flags);
+
 /* Chained block hashes of one prompt (section 4.2 index key; the hash itself is this
  * library's convention): out[i] for i < floor(n_tokens/bs), computed by the device kernel. */
 int mp_block_hashes(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, uint64_t *out,

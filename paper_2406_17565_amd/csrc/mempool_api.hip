@@ -15,6 +15,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -24,7 +25,17 @@
 
 using namespace mempool;
 
+// Block tables of mp_transfer_static: [src ids, MP_STATIC_MAX_BLOCKS][dst ids, MP_STATIC_MAX_BLOCKS]
+// in the library's device image, 512 KiB per GPU, held until the process ends.  In host code
+// this name is only a handle for hipGetSymbolAddress; kernels and copies get the per-device
+// address kept in g_static_tables[].
+static __device__ __align__(256) int32_t scratch[2 * MP_STATIC_MAX_BLOCKS];
+
 namespace {
+
+constexpr int kMaxDevices = 64;
+int32_t *g_static_tables[kMaxDevices] = {};  // device address of `scratch`, per device
+std::mutex g_static_mutex;
 
 enum ProfKind { kProfGather = 0, kProfScatter = 1, kProfDirect = 2, kProfHash = 3, kProfKinds = 4 };
 
@@ -1355,6 +1366,68 @@ int mp_swap_in(mp_pool_t *lower, mp_pool_t *upper, const int32_t *lower_blocks, 
     return rc;
   }
   MP_CATCH(lower)
+}
+
+int mp_transfer_static(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks,
+                       const int32_t *dst_blocks, uint32_t n, uint32_t flags) {
+  // No allocation of any kind on this path: no hipMalloc / hipFree / hipHostMalloc, no stream or
+  // event creation, no std::vector growth.
+  if (!src || !dst) return MP_EINVAL;
+  if ((!src_blocks || !dst_blocks) && n) return fail(src, MP_EINVAL, "null block table");
+  if (flags & ~(MP_DST_GIVEN | MP_ASYNC | MP_DIRECT))
+    return fail(src, MP_EINVAL, "mp_transfer_static takes MP_ASYNC and MP_DIRECT only");
+  if (n > MP_STATIC_MAX_BLOCKS)
+    return fail(src, MP_EINVAL, "more than MP_STATIC_MAX_BLOCKS (65536) table entries");
+  if (!same_geometry(src, dst)) return fail(src, MP_ESHAPE, "source and destination geometry differ");
+  if (src->desc.tier != MP_TIER_HBM || dst->desc.tier != MP_TIER_HBM)
+    return fail(src, MP_ESHAPE, "mp_transfer_static moves blocks between HBM pools only");
+  int rc = check_src_ids(src, src_blocks, n);
+  if (rc != MP_OK) return rc;
+  if (!dst->idx.held_and_distinct(dst_blocks, n))
+    return fail(src, MP_EINVAL, "destination ids must be held and distinct");
+  const bool direct = (flags & MP_DIRECT) != 0;
+  if (!direct && n && (!src->desc.staging || src->desc.staging_bytes < src->B))
+    return fail(src, MP_ENOSTAGING, "staging buffer missing or smaller than one record");
+  if ((rc = check_same_pool(src, dst, src_blocks, dst_blocks, n, flags | MP_DST_GIVEN)) != MP_OK)
+    return rc;
+  if (n == 0) return MP_OK;
+
+  int dev = 0;
+  HIP_TRY(src, hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(src, MP_EINVAL, "device ordinal out of range");
+  int32_t *tables = nullptr;
+  {
+    std::lock_guard<std::mutex> lock(g_static_mutex);
+    if (!g_static_tables[dev])  // once per device, with that device current
+      HIP_TRY(src, hipGetSymbolAddress((void **)&g_static_tables[dev], HIP_SYMBOL(scratch)));
+    tables = g_static_tables[dev];
+  }
+  if (!tables) return fail(src, MP_EHIP, "no device address for the static block tables");
+
+  // Both tables go up on the executing stream, so they are ordered behind the kernels of an
+  // earlier call on the same stream that still read the array.
+  hipStream_t stream = (hipStream_t)src->desc.stream;
+  int32_t *d_src = tables, *d_dst = tables + MP_STATIC_MAX_BLOCKS;
+  HIP_TRY(src, hipMemcpyAsync(d_src, src_blocks, 4ull * n, hipMemcpyHostToDevice, stream));
+  HIP_TRY(src, hipMemcpyAsync(d_dst, dst_blocks, 4ull * n, hipMemcpyHostToDevice, stream));
+  const int n_cus = src->dev.n_cus;
+  if (direct) {
+    HIP_TRY(src, launch_block_copy(pool_side(src, d_src), pool_side(dst, d_dst), n, src->P, src->F,
+                                   src->tune, n_cus, stream));
+  } else {
+    const uint32_t cap = (uint32_t)std::min<uint64_t>(src->desc.staging_bytes / src->B, 0xffffffffu);
+    for (uint32_t first = 0; first < n; first += cap) {
+      const uint32_t cnt = std::min(cap, n - first);
+      HIP_TRY(src, launch_block_copy(pool_side(src, d_src + first),
+                                     record_side(src, src->desc.staging, src->P), cnt, src->P, src->F,
+                                     src->tune, n_cus, stream));
+      HIP_TRY(src, launch_block_copy(record_side(src, src->desc.staging, src->P),
+                                     pool_side(dst, d_dst + first), cnt, src->P, src->F, src->tune,
+                                     n_cus, stream));
+    }
+  }
+  if (!(flags & MP_ASYNC)) HIP_TRY(src, hipStreamSynchronize(stream));
+  return MP_OK;
 }
 
 int mp_gather(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags) {

@@ -20,6 +20,7 @@ MP_DST_GIVEN, MP_EVICT_ON_DEMAND, MP_ASYNC = 0x01, 0x02, 0x04
 MP_MATCH_PIN, MP_TOKENS_ON_DEVICE, MP_DIRECT = 0x08, 0x10, 0x20
 MP_PER_FRAGMENT = 0x40
 PROF_GATHER, PROF_SCATTER, PROF_DIRECT, PROF_HASH = 0, 1, 2, 3
+MP_STATIC_MAX_BLOCKS = 65536
 
 EXPORTS = [
     "mp_pool_create", "mp_pool_destroy", "mp_pool_stats", "mp_last_error", "mp_strerror",
@@ -29,7 +30,7 @@ EXPORTS = [
     "mp_set_recv_callback", "mp_profile_enable", "mp_profile_read", "mp_set_tunable",
     "mp_selftest", "mp_plain_copy", "mp_transfer_layers",
     "mp_block_hashes_batch", "mp_delete", "mp_delete_hashed", "mp_transfer_batch",
-    "mp_swap_out", "mp_swap_in",
+    "mp_swap_out", "mp_swap_in", "mp_transfer_static",
 ]
 
 
@@ -79,6 +80,7 @@ def lib():
             "mp_transfer_with_insert": [vp, vp, vp, u32, u32, vp, vp, u32, u32, vp, u64],
             "mp_transfer_layers": [vp, vp, vp, vp, u32, u32, u32, u32],
             "mp_transfer_batch": [vp, vp, vp, vp, vp, u32, u32],
+            "mp_transfer_static": [vp, vp, vp, vp, u32, u32],
             "mp_match_batch": [vp, vp, vp, u32, vp, vp, vp, u32],
             "mp_transfer_with_insert_batch": [vp, vp, vp, vp, u32, vp, vp, vp, vp, u32],
             "mp_block_hashes": [vp, vp, u32, vp, u32],
@@ -228,6 +230,12 @@ def mp_transfer_layers(src, dst, src_blocks, dst_blocks, layer_begin, layer_end,
     s, d = _i32(src_blocks), _i32(dst_blocks)
     assert s.size == d.size
     return lib().mp_transfer_layers(src, dst, _ptr(s), _ptr(d), s.size, layer_begin, layer_end, flags)
+
+
+def mp_transfer_static(src, dst, src_blocks, dst_blocks, flags=0):
+    s, d = _i32(src_blocks), _i32(dst_blocks)
+    assert s.size == d.size
+    return lib().mp_transfer_static(src, dst, _ptr(s), _ptr(d), s.size, flags)
 
 
 def mp_transfer_with_insert(src, dst, tokens, first_block, src_blocks, dst_blocks=None, flags=0,
