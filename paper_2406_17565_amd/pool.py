@@ -3,6 +3,8 @@
 torch supplies the HBM tensors (pool and staging), the pinned host tensor of a host-tier pool
 and the stream; everything that moves or hashes data is done by the library's kernels.
 """
+import weakref
+
 import numpy as np
 import torch
 
@@ -10,6 +12,34 @@ from . import mempool as M
 
 
 class TorchPool:
+    # Canary bands: with GUARD_BYTES > 0 (a multiple of 256; the GPU tests switch it on) every
+    # pool, staging and pinned-host buffer is allocated with that many extra bytes in front and
+    # behind, filled with GUARD_VALUE; guards_intact() tells whether a copy strayed into them.
+    GUARD_BYTES = 0
+    GUARD_VALUE = 0xA5
+    live = weakref.WeakSet()
+
+    def _buffer(self, nbytes, device=None):
+        g = self._guard
+        if device is None:
+            raw = torch.empty(nbytes + 2 * g, dtype=torch.uint8, pin_memory=True)
+        else:
+            raw = torch.empty(nbytes + 2 * g, dtype=torch.uint8, device=device)
+        if g:
+            raw[:g] = self.GUARD_VALUE
+            raw[g + nbytes:] = self.GUARD_VALUE
+        self._raw.append((raw, nbytes))
+        return raw[g:g + nbytes]
+
+    def guards_intact(self) -> bool:
+        g = self._guard
+        if not g:
+            return True
+        if any(raw.is_cuda for raw, _ in self._raw):
+            torch.cuda.synchronize()
+        return all(bool((raw[:g] == self.GUARD_VALUE).all()) and
+                   bool((raw[g + n:] == self.GUARD_VALUE).all()) for raw, n in self._raw)
+
     def __init__(self, L, H, D, bs, e, NB, tier=M.MP_TIER_HBM, staging_blocks=0, seed=0,
                  instance_id=0, device="cuda:0", stream=None, layout=M.MP_LAYOUT_DEFAULT):
         self.geom = (L, H, D, bs, e)
@@ -19,13 +49,11 @@ class TorchPool:
         self.F = bs * H * D * e
         self.B = 2 * L * self.F
         nbytes = 2 * L * NB * self.F
-        if tier == M.MP_TIER_HBM:
-            self.mem = torch.empty(nbytes, dtype=torch.uint8, device=device)
-        else:
-            self.mem = torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
+        self._guard, self._raw, self.h = self.GUARD_BYTES, [], None
+        self.mem = self._buffer(nbytes, device if tier == M.MP_TIER_HBM else None)
         self.staging = None
         if staging_blocks:
-            self.staging = torch.empty(staging_blocks * self.B, dtype=torch.uint8, device=device)
+            self.staging = self._buffer(staging_blocks * self.B, device)
         self.stream = stream if stream is not None else torch.cuda.current_stream(device)
         rc, self.h = M.mp_pool_create(
             L, H, D, bs, e, NB, self.mem.data_ptr(), tier=tier, instance_id=instance_id,
@@ -35,11 +63,20 @@ class TorchPool:
             stream=self.stream.cuda_stream or None, layout=layout)
         if rc != M.MP_OK:
             raise ValueError(f"mp_pool_create: {M.mp_strerror(rc)}")
+        TorchPool.live.add(self)
 
     def close(self):
         if self.h is not None:
-            M.mp_pool_destroy(self.h)
+            M.mp_pool_destroy(self.h)          # waits for the pool's streams
             self.h = None
+            if not self.guards_intact():
+                raise RuntimeError("a copy wrote outside the pool / staging memory (canary band changed)")
+
+    def free_memory(self):
+        """close(), then drop the tensors (the caller may empty torch's cache afterwards)."""
+        self.close()
+        self.mem = self.staging = None
+        self._raw = []
 
     def __del__(self):
         try:

@@ -8,9 +8,12 @@ At these sizes a dense CPU copy of the pools does not fit a test, so the check i
   * data plane: for a seeded sample of table entries the source blocks are fetched from the
     GPU, pushed through the oracle's own gather / scatter, and compared byte for byte with the
     destination blocks on the GPU;
-  * untouched blocks: 64-bit integer checksums of every (plane, block) fragment of the
-    destination pool, taken on the GPU before and after, must be unchanged outside the
-    destination table.
+  * every entry: a position-weighted 64-bit checksum of EVERY destination fragment named by the
+    table (all entries, all planes), taken on the GPU, must equal the checksum of its source
+    fragment -- so a defect that hits only entries outside the sample (a grid tail, an entry
+    behind a staging-round boundary) cannot pass;
+  * untouched blocks: the same checksums of every (plane, block) fragment of the destination
+    pool, taken before and after, must be unchanged outside the destination table.
 """
 import numpy as np
 import pytest
@@ -41,9 +44,53 @@ def fill_random(pool):
     torch.cuda.synchronize()
 
 
-def checksums(pool):
-    L2 = 2 * pool.geom[0]
-    return pool.mem.view(torch.int64).view(L2, pool.NB, pool.F // 8).sum(dim=2)
+_WEIGHTS = {}
+
+
+def _weights(n_words, device):
+    """One odd 64-bit multiplier per 8-byte word of a fragment, so that words that swap places
+    inside a fragment change the checksum (a plain sum would not notice)."""
+    key = (n_words, str(device))
+    if key not in _WEIGHTS:
+        j = torch.arange(n_words, dtype=torch.int64, device=device)
+        _WEIGHTS[key] = (2 * j + 1) * -7046029254386353131          # 0x9E3779B97F4A7C15, wraps mod 2^64
+    return _WEIGHTS[key]
+
+
+def checksums(pool, ids=None):
+    """[2L, n] checksums sum_j word_j * odd_j (mod 2^64) of the fragments of blocks `ids` (all
+    blocks if None), computed where the pool lives, plane by plane to bound the temporaries."""
+    L2, w = 2 * pool.geom[0], pool.F // 8
+    dev = pool.mem.device
+    idx = None if ids is None else torch.as_tensor(np.asarray(ids, dtype=np.int64), device=dev)
+    n = pool.NB if idx is None else idx.numel()
+    W = _weights(w, dev)
+    out = torch.empty(L2, n, dtype=torch.int64, device=dev)
+    words = pool.mem.view(torch.int64)
+    for p in range(L2):
+        if pool.aggregated:
+            plane = words.view(pool.NB, L2, w)[:, p, :]
+        else:
+            plane = words.view(L2, pool.NB, w)[p]
+        step = max(1, (1 << 27) // w)                                  # 1 GiB of words at a time
+        for lo in range(0, n, step):
+            rows = plane[lo:lo + step] if idx is None else plane[idx[lo:lo + step]]
+            out[p, lo:lo + step] = (rows * W).sum(dim=1)
+    return out
+
+
+def check_all_entries(src, dst, src_tbl, dst_tbl, dst_sums=None):
+    """Every fragment of every table entry arrived: checksum(dst fragment) == checksum(src fragment)."""
+    torch.cuda.synchronize()
+    if len(src_tbl) == 0:
+        return
+    want = checksums(src, src_tbl).cpu()
+    if dst_sums is None:
+        got = checksums(dst, dst_tbl).cpu()
+    else:
+        got = dst_sums[:, torch.as_tensor(np.asarray(dst_tbl, dtype=np.int64), device=dst_sums.device)].cpu()
+    bad = (want != got).nonzero()
+    assert bad.numel() == 0, f"{bad.shape[0]} fragments differ, first (plane, entry) = {bad[0].tolist()}"
 
 
 def blocks_of(pool, ids):
@@ -103,8 +150,7 @@ def make_pools(gpu, g, NB_src, NB_dst, staging_blocks):
 
 def release(*pools):
     for p in pools:
-        p.close()
-        p.mem = p.staging = None
+        p.free_memory()               # also checks the canary bands around pool and staging
     torch.cuda.empty_cache()
 
 
@@ -139,10 +185,10 @@ def test_config3_multiturn_sessions(gpu):
         assert rco == 0 and d.tolist() == d_o.tolist()
         check_sample(geom, src, dst, src_tbl, d, rng)
         after = checksums(dst)
+        check_all_entries(src, dst, src_tbl, d, dst_sums=after)
         untouched = torch.ones(g.NB, dtype=torch.bool, device="cuda")
         untouched[torch.as_tensor(d.astype(np.int64), device="cuda")] = False
         assert torch.equal(before[:, untouched], after[:, untouched])
-        assert not torch.equal(before[:, ~untouched], after[:, ~untouched])
         assert dst.stats() == mir.dst.stats()
         moved.append(len(d))
     # the volumes of the recipe: first turn moves whole prompts, later turns only the new suffix
@@ -173,6 +219,7 @@ def test_config2_lognormal_requests(gpu):
         rco, d_o = O.transfer_with_insert(mir.src, mir.dst, p, 0, tbl)
         assert rc == rco == 0 and d.tolist() == d_o.tolist()
         check_sample(geom, src, dst, tbl, d, rng, k=8)
+        check_all_entries(src, dst, tbl, d)
         assert M.mp_match(dst.h, p, nb)[1].tolist() == mir.dst.match(p)[1].tolist() == d[: len(p) // g.bs].tolist()
     rest = prompts[6:]
     toks, tok_off = W.csr(rest)
@@ -187,6 +234,7 @@ def test_config2_lognormal_requests(gpu):
     assert rc == rco == 0 and d.tolist() == d_o.tolist()
     check_sample(geom, src, dst, tbl, d, rng, k=16)
     after = checksums(dst)
+    check_all_entries(src, dst, tbl, d, dst_sums=after)
     untouched = torch.ones(g.NB, dtype=torch.bool, device="cuda")
     untouched[torch.as_tensor(d.astype(np.int64), device="cuda")] = False
     assert torch.equal(before[:, untouched], after[:, untouched])
@@ -211,11 +259,17 @@ def test_config4_long_context_with_eviction(gpu):
         assert rc == rco == 0 and m.tolist() == mo.tolist()
         tbl = rng.permutation(NB_src)[: nb - len(m)].astype(np.int32)
         fl = M.MP_EVICT_ON_DEMAND | (M.MP_ASYNC if r % 2 else 0)
+        before = checksums(dst) if r % 8 == 0 else None
         rc, d = M.mp_transfer_with_insert(src.h, dst.h, p, len(m), tbl, flags=fl)
         rco, d_o = O.transfer_with_insert(mir.src, mir.dst, p, len(mo), tbl, flags=O.EVICT_ON_DEMAND)
         assert rc == rco == 0 and d.tolist() == d_o.tolist(), M.mp_last_error(src.h)
         if r % 4 == 0:
             check_sample(geom, src, dst, tbl, d, rng, k=4)
+        check_all_entries(src, dst, tbl, d)
+        if before is not None:
+            untouched = torch.ones(NB_dst, dtype=torch.bool, device="cuda")
+            untouched[torch.as_tensor(d.astype(np.int64), device="cuda")] = False
+            assert torch.equal(before[:, untouched], checksums(dst)[:, untouched])
         ids = np.concatenate([m, d])
         assert M.mp_free(dst.h, ids) == mir.dst.free(ids) == 0          # the request finishes
         assert dst.stats() == mir.dst.stats()
@@ -245,6 +299,7 @@ def test_config5_tp_share_and_host_tier(gpu):
     assert rc == rco == 0 and d.tolist() == d_o.tolist(), M.mp_last_error(src.h)
     check_sample(geom, src, dst, tbl, d, rng, k=64)
     after = checksums(dst)
+    check_all_entries(src, dst, tbl, d, dst_sums=after)
     untouched = torch.ones(g.NB, dtype=torch.bool, device="cuda")
     untouched[torch.as_tensor(d.astype(np.int64), device="cuda")] = False
     assert torch.equal(before[:, untouched], after[:, untouched])
@@ -264,11 +319,13 @@ def test_config5_tp_share_and_host_tier(gpu):
     rco, h_o = O.transfer(mir.src, o_host, tbl[pick])
     assert rc == rco == 0 and h_ids.tolist() == h_o.tolist(), M.mp_last_error(src.h)
     check_sample(geom, src, host, tbl[pick], h_ids, rng, k=32)
+    check_all_entries(src, host, tbl[pick], h_ids)
     back = TorchPool(*geom, 2048, staging_blocks=256)
     rc, b_ids = M.mp_transfer(host.h, back.h, h_ids)
     assert rc == 0, M.mp_last_error(host.h)
     check_sample(geom, host, back, h_ids, b_ids, rng, k=32)
     check_sample(geom, src, back, tbl[pick], b_ids, rng, k=32)   # round trip = identity
+    check_all_entries(src, back, tbl[pick], b_ids)
 
     # swap: the receiver's cache moves its 1500 coldest blocks down to a host pool (zero-copy
     # kernel), then one prompt is brought back up
@@ -285,6 +342,7 @@ def test_config5_tp_share_and_host_tier(gpu):
         assert rc == 0 and low_ids.tolist() == o_low.match(prompts[r])[1].tolist() and len(low_ids) == 128
         sl = tbl[r * 128:(r + 1) * 128]
         check_sample(geom, src, low, sl, low_ids, rng, k=32)     # src -> dst -> host tier, bytes intact
+        check_all_entries(src, low, sl, low_ids)
     r = hit[0]
     assert len(M.mp_match(dst.h, prompts[r], 128)[1]) == len(mir.dst.match(prompts[r])[1]) == 0
     low_ids = M.mp_match(low.h, prompts[r], 128)[1]
@@ -295,6 +353,7 @@ def test_config5_tp_share_and_host_tier(gpu):
     assert M.mp_match(dst.h, prompts[r], 128)[1].tolist() == up.tolist()
     mir.dst.match(prompts[r])
     check_sample(geom, src, dst, tbl[r * 128:(r + 1) * 128], up, rng, k=32)
+    check_all_entries(src, dst, tbl[r * 128:(r + 1) * 128], up)
     assert M.mp_free(dst.h, up) == mir.dst.free(up) == 0
     assert dst.stats() == mir.dst.stats() and low.stats() == o_low.stats()
     release(src, dst, host, back, low)
