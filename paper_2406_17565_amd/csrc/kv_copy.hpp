@@ -17,6 +17,7 @@ struct CopySide {
   const int32_t *tbl = nullptr;  // DEVICE pointer, or null for the identity
   uint64_t plane_stride = 0;
   uint64_t block_stride = 0;
+  bool ascending = false;        // the ids in tbl are known to ascend (the host sorted the table)
 };
 
 // Launch shape of the copy kernel.  -1 = choose from the geometry (see default_tune).
@@ -35,13 +36,16 @@ struct CopyTune {
 
 // Fills every field of `t` that is still -1.  Measured on MI355X (sweeps over all five
 // geometries): one 16-byte load per lane and one-wave workgroups give the most bandwidth
-// (many small independent waves beat deep unrolling); walking records is best when one side
-// is contiguous staging or an aggregated pool, walking planes when both sides are discrete
-// pools (fused copy); the per-XCD
-// contiguous walk helps for fragments of 64 KiB and more, and from 16 KiB when the destination
-// is a discrete pool (scattered writes).
+// (many small independent waves beat deep unrolling).  Reads run at the same rate whatever
+// the order of the fragments; WRITES are the sensitive side -- they reach copy speed only
+// when the stores that are in flight together sweep ascending addresses of one plane.  So:
+// when the destination is a discrete pool and its ids ascend (the host sorts the table pair by
+// destination id), walk plane by plane with each XCD on a contiguous eighth of the items;
+// otherwise walk records when one side is contiguous (staging, an aggregated pool) and planes
+// when both sides are discrete pools; the per-XCD contiguous walk then helps for fragments of
+// 64 KiB and more, and from 16 KiB when the destination is a discrete pool.
 CopyTune default_tune(CopyTune t, uint64_t frag_bytes, bool both_sides_discrete_pools,
-                      bool dst_is_discrete_pool);
+                      bool dst_is_discrete_pool, bool dst_ids_ascend);
 
 // Unsigned division by an invariant divisor for numerators below 2^31:
 // x / d == (x * m) >> s.

@@ -69,7 +69,8 @@ struct DeviceCtx {
   int tables_last = -1;           // slot holding `last_ids`, -1 = none
   uint32_t last_n = 0;
   bool last_has_src = false, last_has_dst = false;
-  std::vector<int32_t> last_ids;  // host copy of the last upload: [src n][dst n]
+  int last_sort_by = -1;
+  std::vector<int32_t> last_ids;  // the caller's arrays of the last upload: [src n][dst n]
   MirrorBuf tokens;              // concatenated prompts
   MirrorBuf offsets;             // [tok_off][blk_off]
   MirrorBuf hashes;
@@ -115,6 +116,7 @@ struct mp_pool {
   mp_recv_cb cb = nullptr;
   void *cb_user = nullptr;
   std::vector<int32_t> scratch_ids;
+  std::vector<uint64_t> sort_a, sort_b;  // table sorting
 };
 
 namespace {
@@ -436,17 +438,58 @@ int launch_probe(mp_pool *p, const uint32_t *k_tok, uint32_t n_req, const uint32
 }
 
 // ---- block-table upload -----------------------------------------------------------------------
-// Puts [src ids][dst ids] on the device of `x` (either may be null); device pointers come back.
+// Orders the table pair by one side's ids (results do not depend on the order of the entries;
+// destination ids are distinct).  Keys are (id << 32 | other id); small tables use std::sort,
+// large ones an LSD radix sort over the id bits, so the cost stays a few ns per entry.
+void sort_pairs(mp_pool *x, const int32_t *key_ids, const int32_t *other_ids, uint32_t n,
+                uint32_t key_range, int32_t *key_out, int32_t *other_out) {
+  std::vector<uint64_t> &a = x->sort_a, &b = x->sort_b;
+  a.resize(n);
+  for (uint32_t i = 0; i < n; ++i)
+    a[i] = ((uint64_t)(uint32_t)key_ids[i] << 32) | (uint32_t)other_ids[i];
+  if (n <= 512) {
+    std::sort(a.begin(), a.end());
+  } else {
+    b.resize(n);
+    uint32_t bits = 1;
+    while (bits < 32 && (1ull << bits) < key_range) ++bits;
+    for (uint32_t shift = 32; shift < 32 + bits; shift += 11) {
+      uint32_t count[2049] = {0};
+      for (uint32_t i = 0; i < n; ++i) ++count[((a[i] >> shift) & 2047u) + 1];
+      for (uint32_t d = 0; d < 2048; ++d) count[d + 1] += count[d];
+      for (uint32_t i = 0; i < n; ++i) b[count[(a[i] >> shift) & 2047u]++] = a[i];
+      a.swap(b);
+    }
+  }
+  for (uint32_t i = 0; i < n; ++i) {
+    key_out[i] = (int32_t)(uint32_t)(a[i] >> 32);
+    other_out[i] = (int32_t)(uint32_t)a[i];
+  }
+}
+
+// Puts [src ids][dst ids] on the device of `x` (either may be null); device pointers come back,
+// and host pointers to the same arrays as they were uploaded.  sort_by: -1 keeps the caller's
+// order (the staging order of mp_gather / mp_scatter is part of their contract); 0 / 1 sorts
+// the pair by source / destination id first (both tables must be given).
 int upload_tables(mp_pool *x, const int32_t *src_ids, const int32_t *dst_ids, uint32_t n,
-                  const int32_t **d_src, const int32_t **d_dst) {
+                  const int32_t **d_src, const int32_t **d_dst, int sort_by = -1,
+                  uint32_t key_range = 0, const int32_t **h_src = nullptr,
+                  const int32_t **h_dst = nullptr) {
   DeviceCtx &d = x->dev;
-  // same pair as last time (every layer of a by-layer transfer): nothing to send
+  if (!src_ids || !dst_ids || n < 2) sort_by = -1;
+  auto hand_out = [&](int slot) {
+    const int32_t *h = (const int32_t *)d.tables[slot].host;
+    *d_src = (const int32_t *)d.tables[slot].dev;
+    *d_dst = (const int32_t *)d.tables[slot].dev + n;
+    if (h_src) *h_src = h;
+    if (h_dst) *h_dst = h + n;
+  };
+  // same pair as last time (every layer of a by-layer transfer): nothing to sort or send
   if (d.tables_last >= 0 && d.last_n == n && d.last_has_src == (src_ids != nullptr) &&
-      d.last_has_dst == (dst_ids != nullptr) &&
+      d.last_has_dst == (dst_ids != nullptr) && d.last_sort_by == sort_by &&
       (!src_ids || std::memcmp(d.last_ids.data(), src_ids, 4ull * n) == 0) &&
       (!dst_ids || std::memcmp(d.last_ids.data() + n, dst_ids, 4ull * n) == 0)) {
-    *d_src = (const int32_t *)d.tables[d.tables_last].dev;
-    *d_dst = (const int32_t *)d.tables[d.tables_last].dev + n;
+    hand_out(d.tables_last);
     return MP_OK;
   }
   const int slot = d.tables_next;
@@ -459,25 +502,32 @@ int upload_tables(mp_pool *x, const int32_t *src_ids, const int32_t *dst_ids, ui
   int rc = reserve(x, d.tables[slot], std::max<size_t>(8, 8ull * n));
   if (rc != MP_OK) return rc;
   int32_t *h = (int32_t *)d.tables[slot].host;
-  if (src_ids) std::memcpy(h, src_ids, 4ull * n);
-  if (dst_ids) std::memcpy(h + n, dst_ids, 4ull * n);
+  if (sort_by == 0) sort_pairs(x, src_ids, dst_ids, n, key_range, h, h + n);
+  else if (sort_by == 1) sort_pairs(x, dst_ids, src_ids, n, key_range, h + n, h);
+  else {
+    if (src_ids) std::memcpy(h, src_ids, 4ull * n);
+    if (dst_ids) std::memcpy(h + n, dst_ids, 4ull * n);
+  }
   HIP_TRY(x, hipMemcpyAsync(d.tables[slot].dev, h, 8ull * n, hipMemcpyHostToDevice, d.stream));
   HIP_TRY(x, hipEventRecord(d.tables_uploaded[slot], d.stream));
   d.tables_pending[slot] = true;
-  d.last_ids.assign(h, h + 2ull * n);
+  d.last_ids.resize(2ull * n);  // the caller's own arrays: what the next call is compared with
+  if (src_ids) std::memcpy(d.last_ids.data(), src_ids, 4ull * n);
+  if (dst_ids) std::memcpy(d.last_ids.data() + n, dst_ids, 4ull * n);
   d.last_n = n;
   d.last_has_src = src_ids != nullptr;
   d.last_has_dst = dst_ids != nullptr;
+  d.last_sort_by = sort_by;
   d.tables_last = slot;
-  *d_src = (const int32_t *)d.tables[slot].dev;
-  *d_dst = (const int32_t *)d.tables[slot].dev + n;
+  hand_out(slot);
   return MP_OK;
 }
 
 // `l0` = first layer addressed (by-layer transfers start in the middle of a block's planes).
-CopySide pool_side(const mp_pool *p, const int32_t *d_tbl, uint32_t l0 = 0) {
+CopySide pool_side(const mp_pool *p, const int32_t *d_tbl, uint32_t l0 = 0, bool ascending = false) {
   CopySide s;
   s.tbl = d_tbl;
+  s.ascending = ascending;
   if (!aggregated(p)) {  // discrete layout [L][2][NB][F]
     s.plane_stride = (uint64_t)p->desc.n_blocks * p->F;
     s.block_stride = p->F;
@@ -536,10 +586,21 @@ int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *
   const uint64_t B = (uint64_t)planes * x->F;  // bytes moved per table entry
   const int32_t *d_src = nullptr, *d_dst = nullptr;
   const bool direct = (flags & MP_DIRECT) != 0;
+  bool dst_ascends = false;
   if (!(flags & MP_PER_FRAGMENT)) {
-    rc = upload_tables(x, (s_hbm || direct) ? src_ids : nullptr, (d_hbm || direct) ? dst_ids : nullptr,
-                       n, &d_src, &d_dst);
+    // The pair of tables is sorted before it goes up (the result does not depend on the order
+    // of the entries): by destination id, so that the stores of a launch sweep each plane of
+    // the destination pool upwards -- the write pattern HBM takes at copy speed --; or, when the
+    // copy engine moves the records of a host pool, by that pool's ids, so that runs of
+    // consecutive ids merge into single copies.
+    const int sort_by = (!direct && !s_hbm) ? 0 : 1;
+    const int32_t *h_src = src_ids, *h_dst = dst_ids;
+    rc = upload_tables(x, src_ids, dst_ids, n, &d_src, &d_dst, sort_by,
+                       sort_by ? dst->desc.n_blocks : src->desc.n_blocks, &h_src, &h_dst);
     if (rc != MP_OK) return rc;
+    src_ids = h_src;  // from here on: the order the device tables (and staging) have
+    dst_ids = h_dst;
+    dst_ascends = sort_by == 1;
   }
 
   if (flags & MP_PER_FRAGMENT) {
@@ -561,8 +622,8 @@ int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *
     // reads or writes host memory through the host link itself (zero-copy): no staging write,
     // no copy-engine hop.
     ProfScope ps(x, kProfDirect, 2ull * n * B);
-    HIP_TRY(x, launch_block_copy(pool_side(src, d_src, l0), pool_side(dst, d_dst, l0), n, planes,
-                                 x->F, tune, d.n_cus, d.stream));
+    HIP_TRY(x, launch_block_copy(pool_side(src, d_src, l0), pool_side(dst, d_dst, l0, dst_ascends), n,
+                                 planes, x->F, tune, d.n_cus, d.stream));
     return MP_OK;
   }
 
@@ -580,8 +641,8 @@ int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *
       {
         ProfScope ps(x, kProfScatter, 2ull * cnt * B);
         HIP_TRY(x, launch_block_copy(record_side(x, staging, planes),
-                                     pool_side(dst, d_dst + first, l0), cnt, planes, x->F, tune,
-                                     d.n_cus, d.stream));
+                                     pool_side(dst, d_dst + first, l0, dst_ascends), cnt, planes,
+                                     x->F, tune, d.n_cus, d.stream));
       }
     }
     return MP_OK;
@@ -1411,9 +1472,11 @@ int mp_transfer_static(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks
   HIP_TRY(src, hipMemcpyAsync(d_src, src_blocks, 4ull * n, hipMemcpyHostToDevice, stream));
   HIP_TRY(src, hipMemcpyAsync(d_dst, dst_blocks, 4ull * n, hipMemcpyHostToDevice, stream));
   const int n_cus = src->dev.n_cus;
+  bool ascends = true;  // nothing is sorted here (no host buffer to sort into): take what the caller gives
+  for (uint32_t i = 1; i < n && ascends; ++i) ascends = dst_blocks[i] > dst_blocks[i - 1];
   if (direct) {
-    HIP_TRY(src, launch_block_copy(pool_side(src, d_src), pool_side(dst, d_dst), n, src->P, src->F,
-                                   src->tune, n_cus, stream));
+    HIP_TRY(src, launch_block_copy(pool_side(src, d_src), pool_side(dst, d_dst, 0, ascends), n, src->P,
+                                   src->F, src->tune, n_cus, stream));
   } else {
     const uint32_t cap = (uint32_t)std::min<uint64_t>(src->desc.staging_bytes / src->B, 0xffffffffu);
     for (uint32_t first = 0; first < n; first += cap) {
@@ -1422,8 +1485,8 @@ int mp_transfer_static(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks
                                      record_side(src, src->desc.staging, src->P), cnt, src->P, src->F,
                                      src->tune, n_cus, stream));
       HIP_TRY(src, launch_block_copy(record_side(src, src->desc.staging, src->P),
-                                     pool_side(dst, d_dst + first), cnt, src->P, src->F, src->tune,
-                                     n_cus, stream));
+                                     pool_side(dst, d_dst + first, 0, ascends), cnt, src->P, src->F,
+                                     src->tune, n_cus, stream));
     }
   }
   if (!(flags & MP_ASYNC)) HIP_TRY(src, hipStreamSynchronize(stream));
