@@ -119,16 +119,26 @@ def run_step(M, src, dst, turn, perm, state, flags):
 
 
 def cpu_baseline(W, geom, n_sessions=64, n_turns=4, NB_src=4096, NB_dst=8704):
-    """The CPU oracle on a bounded sample of the same workload: the four turns of the first two
-    sets of sessions, same geometry, pools cut to what one set needs; single thread."""
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: the four turns of
+    the first two sets of sessions, same geometry, pools cut to what one set needs.  One thread,
+    pinned to one core; the copy part (transfer_with_insert: allocation, memcpy by table, trie
+    insert) and the hash + match part (chained block hashes of every prompt, trie walk) are timed
+    separately."""
     from oracle import oracle as O
+    pinned_to = None
+    try:
+        cores = sorted(os.sched_getaffinity(0))
+        os.sched_setaffinity(0, {cores[-1]})
+        pinned_to = cores[-1]
+    except (AttributeError, OSError):
+        cores = None
     rng = np.random.default_rng(3)
     chunk = rng.integers(0, 256, 64 << 20, dtype=np.uint8)
     src_data = np.tile(chunk, geom.pool_bytes(NB_src) // chunk.size)
     src = O.OraclePool(geom.L, geom.H, geom.D, geom.bs, geom.e, NB_src, data=src_data)
     src.alloc(NB_src)
     moved = hashed = 0
-    t_total = 0.0
+    t_copy = t_match = 0.0
     n_epochs = 2                    # about 10 s of single-thread work
     for epoch in range(n_epochs):
         dst = O.OraclePool(geom.L, geom.H, geom.D, geom.bs, geom.e, NB_dst)   # a fresh receiver
@@ -137,32 +147,40 @@ def cpu_baseline(W, geom, n_sessions=64, n_turns=4, NB_src=4096, NB_dst=8704):
             ms = []
             for r in range(n_sessions):
                 t = turn["toks"][turn["tok_off"][r]:turn["tok_off"][r + 1]]
+                O.block_hashes(t, geom.bs, 0)
                 ms.append(len(dst.match(t, flags=O.MATCH_PIN)[1]))
-            t_total += time.perf_counter() - t0
+            t_match += time.perf_counter() - t0
             need = turn["nblk"] - np.array(ms, dtype=np.uint32)
             blk_off = np.concatenate([[0], np.cumsum(need)]).astype(np.uint32)
             src_blocks = rng.permutation(NB_src)[: int(blk_off[-1])].astype(np.int32)
             t0 = time.perf_counter()
             rc, d = O.transfer_with_insert_batch(src, dst, turn["toks"], turn["tok_off"], ms, src_blocks,
                                                  blk_off, flags=O.EVICT_ON_DEMAND)
-            t_total += time.perf_counter() - t0
+            t_copy += time.perf_counter() - t0
             assert rc == 0
             moved += int(blk_off[-1])
             hashed += int(sum(len(turn["toks"][turn["tok_off"][r]:turn["tok_off"][r + 1]]) // geom.bs
                               for r in range(n_sessions)))
         del dst
+    if cores is not None:
+        os.sched_setaffinity(0, set(cores))
     model = ""
     try:
         with open("/proc/cpuinfo") as f:
             model = next((ln.split(":", 1)[1].strip() for ln in f if ln.startswith("model name")), "")
     except OSError:
         pass
+    t_total = t_copy + t_match
     return dict(value=moved * geom.B / t_total / 1e9, unit="GB/s", cores=1, kind="oracle",
-                host_cpu=model, host_cores_visible=os.cpu_count(),
+                pinned_to_core=pinned_to, host_cpu=model, host_cores_visible=os.cpu_count(),
                 sample=f"config 3, the {n_turns} turns of {n_epochs} sets of {n_sessions} sessions "
                        f"({moved} blocks = {moved * geom.B / 2**30:.2f} GiB payload, {hashed} blocks "
                        f"hashed+matched), pools reduced to {NB_src}/{NB_dst} blocks",
-                seconds=round(t_total, 3), blocks_per_s=round(moved / t_total, 1))
+                seconds=round(t_total, 3), blocks_per_s=round(moved / t_total, 1),
+                copy={"GBs": round(moved * geom.B / t_copy / 1e9, 2), "seconds": round(t_copy, 3),
+                      "what": "transfer_with_insert: allocation, gather + scatter by memcpy, trie insert"},
+                hash_match={"blocks_per_s": round(hashed / t_match, 1), "seconds": round(t_match, 4),
+                            "what": "chained block hashes of every prompt + trie walk (match)"})
 
 
 def host_tier(args):
@@ -533,13 +551,19 @@ def main():
     M.mp_profile_enable(src.h, True)
     M.mp_profile_enable(dst.h, True)
     moved = hashed = 0
+    # per-step device times: an event on the executing (source) stream behind every step; the
+    # host may run ahead of the GPU, the gaps between events are what the GPU spent per step
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    marks[0].record(src.stream)
     t0 = time.perf_counter()
-    for i in range(args.warmup, total_steps):
+    for k, i in enumerate(range(args.warmup, total_steps)):
         mv, hs = do_step(i)
+        marks[k + 1].record(src.stream)
         moved += mv
         hashed += hs
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    step_ms = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps))
 
     # match on its own: the batches of the last two steps are fully indexed at the destination,
     # so every block is hashed (kernel) and probed (host).  Two batches alternate because the
@@ -611,15 +635,24 @@ def main():
                  "kernel_GBs": round(f_bytes / (f_ms * 1e-3) / 1e9, 1) if f_ms else None,
                  "path": "direct (fused pool->pool, MP_DIRECT)"}
 
-    # measured HBM traffic per algorithmic byte, from the rocprofv3 FETCH_SIZE / WRITE_SIZE runs
-    # whose summary is committed under profiles/ (counters cannot be read from inside this run)
+    # HBM traffic per launch.  Counters cannot be read from inside this run: the figure is
+    # DERIVED from the committed rocprofv3 FETCH_SIZE / WRITE_SIZE summary of this same command
+    # (bytes fetched + written per algorithmic byte, per kernel kind) times this run's algorithmic
+    # bytes -- and only if that summary was made with the kernel source as it is now; else null.
     traffic = traffic_src = None
-    tpath = os.path.join(ROOT, "profiles", f"kv_block_copy_config{args.config}_"
-                         f"{'direct' if args.direct else 'staged'}_hbm_traffic.json")
+    tpath = os.path.join(ROOT, "profiles", f"kv_block_copy_config{args.config}_hbm_traffic.json")
     if os.path.exists(tpath) and k_n:
+        import profile_summary
         with open(tpath) as f:
-            traffic = int(json.load(f)["traffic_per_algorithmic_byte"] * k_bytes / k_n)
-        traffic_src = os.path.relpath(tpath, ROOT)
+            tj = json.load(f)
+        ratios = tj.get("traffic_per_algorithmic_byte", {})
+        names = {M.PROF_DIRECT: "fused", M.PROF_GATHER: "gather", M.PROF_SCATTER: "scatter"}
+        if tj.get("kernel_source_sha") == profile_summary.kernel_sha() and all(names[k] in ratios for k in kinds):
+            traffic = int(sum(ratios[names[k]] * per_kind[k][2] for k in kinds) / k_n)
+            traffic_src = (f"derived: {os.path.relpath(tpath, ROOT)} (rocprofv3 counter ratio of this "
+                           f"command, same kernel source) x this run's algorithmic bytes")
+        else:
+            traffic_src = "null: the committed counter summary was made with a different kernel source"
 
     payload = moved * geom.B
     out = {
@@ -630,6 +663,11 @@ def main():
         "steps": args.steps,
         "warmup": args.warmup,
         "ms_per_step": round(dt / args.steps * 1e3, 4),
+        "median_ms": round(step_ms[len(step_ms) // 2], 4),
+        "min_ms": round(step_ms[0], 4),
+        "max_ms": round(step_ms[-1], 4),
+        "step_times": "device time between events recorded on the source stream behind every step "
+                      "(steps differ in size: turn 1 of a session set moves about half of what turns 2-4 move)",
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,

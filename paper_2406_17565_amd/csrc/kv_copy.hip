@@ -28,14 +28,14 @@ FastDiv make_fastdiv(uint32_t d) {
 }
 
 CopyTune default_tune(CopyTune t, uint64_t frag_bytes, bool both_sides_discrete_pools,
-                      bool dst_is_discrete_pool, bool dst_ids_ascend) {
+                      bool dst_is_discrete_pool, bool dst_ids_ascend, bool both_sides_tables) {
   const bool sweep = dst_is_discrete_pool && dst_ids_ascend;  // stores ascend inside each plane
   if (t.order < 0) t.order = (sweep || both_sides_discrete_pools) ? 1 : 0;
   if (t.plane_tile < 0) t.plane_tile = 0;  // 0: what `order` says
   if (t.unroll < 0) t.unroll = 1;
   if (t.wg_per_cu < 0) t.wg_per_cu = 0;
   if (t.nontemporal < 0) t.nontemporal = 1;
-  if (t.waves_per_wg < 0) t.waves_per_wg = 1;
+  if (t.waves_per_wg < 0) t.waves_per_wg = (both_sides_tables && frag_bytes < (64u << 10)) ? 4 : 1;
   if (t.xcd_contiguous < 0)
     t.xcd_contiguous = (sweep || frag_bytes >= (64u << 10) ||
                         (frag_bytes >= (16u << 10) && dst_is_discrete_pool)) ? 1 : 0;
@@ -73,19 +73,15 @@ struct CopyArgs {
   FastDiv by_entries;  // / n_entries
 };
 
-// The tables are separate restrict-qualified read-only arguments so that the wave-uniform
-// id loads can be issued as scalar loads.  (A table never aliases pool or staging memory.)
 // W = wavefronts per workgroup.  Workgroups are dealt round-robin to the 8 XCDs in launch
 // order; with a.xcd_span > 0 the workgroup index is re-mapped so that each XCD walks one
 // contiguous eighth of the item space instead of every eighth item.
 // KIND says which sides have a table, so the id fetch is decided at compile time -- and a
-// kernel trace tells the three uses apart by name.
+// kernel trace tells the three uses apart by name.  IDS supplies the (wave-uniform) ids.
 enum CopyKind { kGather = 0 /* table on src */, kScatter = 1 /* on dst */, kFused = 2 /* both */,
                 kRecords = 3 /* neither */ };
-template <int U, bool NT, int W, int KIND>
-__global__ __launch_bounds__(64 * W) void kv_block_copy(const CopyArgs a,
-                                                        const int32_t *__restrict__ src_tbl,
-                                                        const int32_t *__restrict__ dst_tbl) {
+template <int U, bool NT, int W, int KIND, class IDS>
+__device__ __forceinline__ void copy_items(const CopyArgs &a, const IDS &ids) {
   const uint32_t lane = threadIdx.x & 63u;
   const uint32_t wave = W == 1 ? 0u : __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t step = gridDim.x * W;
@@ -101,8 +97,8 @@ __global__ __launch_bounds__(64 * W) void kv_block_copy(const CopyArgs a,
     const uint32_t i = q2 - tile * a.by_entries.d;   // table entry
     const uint32_t p = tile * a.by_tile.d + p_in;    // plane = layer * 2 + (K|V)
     const bool s_tbl = KIND == kGather || KIND == kFused, d_tbl = KIND == kScatter || KIND == kFused;
-    const uint32_t sid = __builtin_amdgcn_readfirstlane(s_tbl ? (uint32_t)src_tbl[i] : i);
-    const uint32_t did = __builtin_amdgcn_readfirstlane(d_tbl ? (uint32_t)dst_tbl[i] : i);
+    const uint32_t sid = __builtin_amdgcn_readfirstlane(s_tbl ? ids.src(i) : i);
+    const uint32_t did = __builtin_amdgcn_readfirstlane(d_tbl ? ids.dst(i) : i);
     const u32x4 *s = reinterpret_cast<const u32x4 *>(a.src_base + p * a.src_plane_stride +
                                                      sid * a.src_block_stride);
     u32x4 *d = reinterpret_cast<u32x4 *>(a.dst_base + p * a.dst_plane_stride +
@@ -123,6 +119,35 @@ __global__ __launch_bounds__(64 * W) void kv_block_copy(const CopyArgs a,
       }
     }
   }
+}
+
+// Ids from tables in device memory.  The tables are separate restrict-qualified read-only
+// kernel arguments so that the wave-uniform id loads can be issued as scalar loads.  (A table
+// never aliases pool or staging memory.)
+struct MemoryIds {
+  const int32_t *__restrict__ s;
+  const int32_t *__restrict__ d;
+  __device__ uint32_t src(uint32_t i) const { return (uint32_t)s[i]; }
+  __device__ uint32_t dst(uint32_t i) const { return (uint32_t)d[i]; }
+};
+template <int U, bool NT, int W, int KIND>
+__global__ __launch_bounds__(64 * W) void kv_block_copy(const CopyArgs a,
+                                                        const int32_t *__restrict__ src_tbl,
+                                                        const int32_t *__restrict__ dst_tbl) {
+  copy_items<U, NT, W, KIND>(a, MemoryIds{src_tbl, dst_tbl});
+}
+
+// Ids from tables that travel in the kernel arguments (a transfer of one request: a few dozen
+// entries): nothing has to be copied to the device before the launch.  The ids are read with
+// scalar loads from the kernel-argument segment.
+struct ArgumentIds {
+  const SmallTables &t;
+  __device__ uint32_t src(uint32_t i) const { return (uint32_t)t.src[i]; }
+  __device__ uint32_t dst(uint32_t i) const { return (uint32_t)t.dst[i]; }
+};
+template <int W, int KIND>
+__global__ __launch_bounds__(64 * W) void kv_block_copy_args(const CopyArgs a, const SmallTables t) {
+  copy_items<1, true, W, KIND>(a, ArgumentIds{t});
 }
 
 // Contiguous copy with the default per-lane shape of the table-driven kernel (one-wave
@@ -174,72 +199,138 @@ hipError_t launch_plain_copy(void *dst, const void *src, uint64_t bytes, hipStre
   return hipGetLastError();
 }
 
+namespace {
+
+// Launch geometry of one launch over entries [first, first + cnt).
+struct Launch {
+  CopyArgs a;
+  uint32_t wgs = 0, W = 1;
+  int U = 1;
+  bool nt = true;
+};
+
+hipError_t check_sides(const CopySide &src, const CopySide &dst, uint32_t n_planes,
+                       uint64_t frag_bytes) {
+  if (!src.base || !dst.base || n_planes == 0 || frag_bytes == 0 || (frag_bytes & 15u) ||
+      (frag_bytes >> 4) > 0x7fffffffull)
+    return hipErrorInvalidValue;
+  return hipSuccess;
+}
+
+CopyTune tune_for(const CopySide &src, const CopySide &dst, bool src_tbl, bool dst_tbl,
+                  uint64_t frag_bytes, const CopyTune &tune_in) {
+  // plane-major walking pays off only when both ends are discrete-layout pools
+  const bool both_discrete = src_tbl && dst_tbl && src.plane_stride > src.block_stride &&
+                             dst.plane_stride > dst.block_stride;
+  const bool dst_discrete = dst_tbl && dst.plane_stride > dst.block_stride;
+  return default_tune(tune_in, frag_bytes, both_discrete, dst_discrete, dst.ascending,
+                      src_tbl && dst_tbl);
+}
+
+Launch prepare(const CopySide &src, const CopySide &dst, bool src_tbl, bool dst_tbl, uint32_t first,
+               uint32_t cnt, uint32_t n_planes, uint64_t frag_bytes, const CopyTune &tune, int U,
+               int n_cus) {
+  Launch l;
+  CopyArgs &a = l.a;
+  const uint32_t frag_vecs = (uint32_t)(frag_bytes >> 4);
+  const uint32_t chunks = (frag_vecs + 64u * U - 1) / (64u * U);
+  // a table-less side addresses entry i directly, so shift its base instead of its table
+  a.src_base = (const uint8_t *)src.base + (src_tbl ? 0 : (uint64_t)first * src.block_stride);
+  a.dst_base = (uint8_t *)dst.base + (dst_tbl ? 0 : (uint64_t)first * dst.block_stride);
+  a.src_plane_stride = src.plane_stride;
+  a.src_block_stride = src.block_stride;
+  a.dst_plane_stride = dst.plane_stride;
+  a.dst_block_stride = dst.block_stride;
+  a.n_items = (uint32_t)((uint64_t)n_planes * chunks * cnt);
+  a.frag_vecs = frag_vecs;
+  a.n_planes = n_planes;
+  a.n_entries = cnt;
+  a.by_chunks = make_fastdiv(chunks);
+  uint32_t tile_planes = tune.plane_tile > 0 ? std::min<uint32_t>((uint32_t)tune.plane_tile, n_planes)
+                                             : (tune.order == 0 ? n_planes : 1u);
+  while (n_planes % tile_planes) --tile_planes;  // a divisor of the plane count
+  a.by_tile = make_fastdiv(tile_planes);
+  a.by_entries = make_fastdiv(cnt);
+  l.W = tune.waves_per_wg == 1 ? 1u : 4u;
+  l.wgs = (a.n_items + l.W - 1u) / l.W;
+  if (tune.wg_per_cu > 0) {
+    const uint64_t cap = (uint64_t)tune.wg_per_cu * (uint64_t)(n_cus > 0 ? n_cus : 256);
+    if (l.wgs > cap) l.wgs = (uint32_t)cap;
+  }
+  a.xcd_span = tune.xcd_contiguous ? l.wgs / 8u : 0u;
+  l.U = U;
+  l.nt = tune.nontemporal != 0;
+  return l;
+}
+
+template <int W>
+hipError_t launch_args_kind(const Launch &l, const SmallTables &t, bool st, bool dt,
+                            hipStream_t stream) {
+  const dim3 grid(l.wgs), block(64 * W);
+  if (st && dt) hipLaunchKernelGGL((kv_block_copy_args<W, kFused>), grid, block, 0, stream, l.a, t);
+  else if (st) hipLaunchKernelGGL((kv_block_copy_args<W, kGather>), grid, block, 0, stream, l.a, t);
+  else hipLaunchKernelGGL((kv_block_copy_args<W, kScatter>), grid, block, 0, stream, l.a, t);
+  return hipGetLastError();
+}
+
+}  // namespace
+
 hipError_t launch_block_copy(const CopySide &src, const CopySide &dst, uint32_t n,
                              uint32_t n_planes, uint64_t frag_bytes, const CopyTune &tune_in,
                              int n_cus, hipStream_t stream) {
   if (n == 0) return hipSuccess;
-  // plane-major walking pays off only when both ends are discrete-layout pools
-  const bool both_discrete = src.tbl != nullptr && dst.tbl != nullptr &&
-                             src.plane_stride > src.block_stride &&
-                             dst.plane_stride > dst.block_stride;
-  const bool dst_discrete = dst.tbl != nullptr && dst.plane_stride > dst.block_stride;
-  const CopyTune tune = default_tune(tune_in, frag_bytes, both_discrete, dst_discrete, dst.ascending);
-  if (!src.base || !dst.base || n_planes == 0 || frag_bytes == 0 || (frag_bytes & 15u) ||
-      (frag_bytes >> 4) > 0x7fffffffull)
-    return hipErrorInvalidValue;
+  if (check_sides(src, dst, n_planes, frag_bytes) != hipSuccess) return hipErrorInvalidValue;
+  const CopyTune tune =
+      tune_for(src, dst, src.tbl != nullptr, dst.tbl != nullptr, frag_bytes, tune_in);
   int U = tune.unroll;
   if (U != 1 && U != 2 && U != 4 && U != 8) return hipErrorInvalidValue;
   const uint32_t frag_vecs = (uint32_t)(frag_bytes >> 4);
   while (U > 1 && 64u * (U / 2) >= frag_vecs) U /= 2;  // no wider than the fragment
   const uint32_t chunks = (frag_vecs + 64u * U - 1) / (64u * U);
   const uint64_t per_entry = (uint64_t)n_planes * chunks;
+  if (per_entry > 0x7fffffffull) return hipErrorInvalidValue;
 
   // keep every item index below 2^31: split very large tables into several launches
   const uint64_t item_cap = tune.item_limit > 0 ? (uint64_t)tune.item_limit : 0x7fffffffull;
   const uint32_t max_entries = (uint32_t)std::max<uint64_t>(item_cap / per_entry, 1);
-  if (per_entry > 0x7fffffffull) return hipErrorInvalidValue;
 
   for (uint32_t first = 0; first < n; first += max_entries) {
     const uint32_t cnt = (n - first < max_entries) ? n - first : max_entries;
-    CopyArgs a;
-    // a table-less side addresses entry i directly, so shift its base instead of its table
-    a.src_base = (const uint8_t *)src.base + (src.tbl ? 0 : (uint64_t)first * src.block_stride);
-    a.dst_base = (uint8_t *)dst.base + (dst.tbl ? 0 : (uint64_t)first * dst.block_stride);
+    const Launch l = prepare(src, dst, src.tbl != nullptr, dst.tbl != nullptr, first, cnt, n_planes,
+                             frag_bytes, tune, U, n_cus);
     const int32_t *st = src.tbl ? src.tbl + first : nullptr;
     const int32_t *dt = dst.tbl ? dst.tbl + first : nullptr;
-    a.src_plane_stride = src.plane_stride;
-    a.src_block_stride = src.block_stride;
-    a.dst_plane_stride = dst.plane_stride;
-    a.dst_block_stride = dst.block_stride;
-    a.n_items = (uint32_t)(per_entry * cnt);
-    a.frag_vecs = frag_vecs;
-    a.n_planes = n_planes;
-    a.n_entries = cnt;
-    a.by_chunks = make_fastdiv(chunks);
-    uint32_t tile_planes = tune.plane_tile > 0 ? std::min<uint32_t>((uint32_t)tune.plane_tile, n_planes)
-                                               : (tune.order == 0 ? n_planes : 1u);
-    while (n_planes % tile_planes) --tile_planes;  // a divisor of the plane count
-    a.by_tile = make_fastdiv(tile_planes);
-    a.by_entries = make_fastdiv(cnt);
-    const uint32_t W = tune.waves_per_wg == 1 ? 1u : 4u;
-    uint32_t wgs = (a.n_items + W - 1u) / W;
-    if (tune.wg_per_cu > 0) {
-      const uint64_t cap = (uint64_t)tune.wg_per_cu * (uint64_t)(n_cus > 0 ? n_cus : 256);
-      if (wgs > cap) wgs = (uint32_t)cap;
-    }
-    a.xcd_span = tune.xcd_contiguous ? wgs / 8u : 0u;
-    const dim3 grid(wgs);
-    const bool nt = tune.nontemporal != 0;
+    const dim3 grid(l.wgs);
     hipError_t e;
     switch (U) {
-      case 1: e = launch_waves<1>(a, st, dt, (int)W, nt, grid, stream); break;
-      case 2: e = launch_waves<2>(a, st, dt, (int)W, nt, grid, stream); break;
-      case 4: e = launch_waves<4>(a, st, dt, (int)W, nt, grid, stream); break;
-      default: e = launch_waves<8>(a, st, dt, (int)W, nt, grid, stream); break;
+      case 1: e = launch_waves<1>(l.a, st, dt, (int)l.W, l.nt, grid, stream); break;
+      case 2: e = launch_waves<2>(l.a, st, dt, (int)l.W, l.nt, grid, stream); break;
+      case 4: e = launch_waves<4>(l.a, st, dt, (int)l.W, l.nt, grid, stream); break;
+      default: e = launch_waves<8>(l.a, st, dt, (int)l.W, l.nt, grid, stream); break;
     }
     if (e != hipSuccess) return e;
   }
   return hipSuccess;
+}
+
+bool small_copy_possible(uint32_t n, uint32_t n_planes, uint64_t frag_bytes, const CopyTune &tune) {
+  const uint64_t chunks = ((frag_bytes >> 4) + 63u) / 64u;
+  return n >= 1 && n <= kSmallTable && tune.unroll < 0 && tune.nontemporal < 0 &&
+         tune.wg_per_cu < 0 && tune.item_limit == 0 &&
+         (uint64_t)n * n_planes * chunks <= 0x7fffffffull;
+}
+
+hipError_t launch_block_copy_small(const CopySide &src, const CopySide &dst, const SmallTables &ids,
+                                   bool src_tbl, bool dst_tbl, uint32_t n, uint32_t n_planes,
+                                   uint64_t frag_bytes, const CopyTune &tune_in, int n_cus,
+                                   hipStream_t stream) {
+  if (!small_copy_possible(n, n_planes, frag_bytes, tune_in) || (!src_tbl && !dst_tbl) ||
+      check_sides(src, dst, n_planes, frag_bytes) != hipSuccess)
+    return hipErrorInvalidValue;
+  const CopyTune tune = tune_for(src, dst, src_tbl, dst_tbl, frag_bytes, tune_in);
+  const Launch l = prepare(src, dst, src_tbl, dst_tbl, 0, n, n_planes, frag_bytes, tune, 1, n_cus);
+  return l.W == 1 ? launch_args_kind<1>(l, ids, src_tbl, dst_tbl, stream)
+                  : launch_args_kind<4>(l, ids, src_tbl, dst_tbl, stream);
 }
 
 }  // namespace mempool

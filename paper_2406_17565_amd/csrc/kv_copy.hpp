@@ -43,9 +43,11 @@ struct CopyTune {
 // destination id), walk plane by plane with each XCD on a contiguous eighth of the items;
 // otherwise walk records when one side is contiguous (staging, an aggregated pool) and planes
 // when both sides are discrete pools; the per-XCD contiguous walk then helps for fragments of
-// 64 KiB and more, and from 16 KiB when the destination is a discrete pool.
+// 64 KiB and more, and from 16 KiB when the destination is a discrete pool.  The fused copy
+// (a table on both sides) of fragments below 64 KiB is 4 % faster with four waves per workgroup
+// (4 KiB of one fragment stay on one CU); everything else is fastest with one.
 CopyTune default_tune(CopyTune t, uint64_t frag_bytes, bool both_sides_discrete_pools,
-                      bool dst_is_discrete_pool, bool dst_ids_ascend);
+                      bool dst_is_discrete_pool, bool dst_ids_ascend, bool both_sides_tables);
 
 // Unsigned division by an invariant divisor for numerators below 2^31:
 // x / d == (x * m) >> s.
@@ -62,6 +64,23 @@ __host__ __device__ inline uint32_t fastdiv(uint32_t x, const FastDiv &f) {
 hipError_t launch_block_copy(const CopySide &src, const CopySide &dst, uint32_t n,
                              uint32_t n_planes, uint64_t frag_bytes, const CopyTune &tune,
                              int n_cus, hipStream_t stream);
+
+// A transfer of one request has a few dozen table entries: its ids travel in the kernel
+// arguments, so no table has to be copied to the device before the launch.
+constexpr uint32_t kSmallTable = 192;
+struct SmallTables {
+  int32_t src[kSmallTable];
+  int32_t dst[kSmallTable];
+};
+// Can launch_block_copy_small take this copy?  (n within the argument tables, default launch
+// shape apart from the walk order)
+bool small_copy_possible(uint32_t n, uint32_t n_planes, uint64_t frag_bytes, const CopyTune &tune);
+// The same copy as launch_block_copy with the ids of the sides that have a table (src_tbl /
+// dst_tbl) taken from `ids`; CopySide::tbl is ignored.
+hipError_t launch_block_copy_small(const CopySide &src, const CopySide &dst, const SmallTables &ids,
+                                   bool src_tbl, bool dst_tbl, uint32_t n, uint32_t n_planes,
+                                   uint64_t frag_bytes, const CopyTune &tune, int n_cus,
+                                   hipStream_t stream);
 
 // Contiguous device-to-device copy of `bytes` (a multiple of 16): the calibration yardstick.
 hipError_t launch_plain_copy(void *dst, const void *src, uint64_t bytes, hipStream_t stream);

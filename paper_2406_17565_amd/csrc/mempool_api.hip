@@ -117,6 +117,8 @@ struct mp_pool {
   void *cb_user = nullptr;
   std::vector<int32_t> scratch_ids;
   std::vector<uint64_t> sort_a, sort_b;  // table sorting
+  std::vector<uint32_t> twi_hoff, twi_ids_off, twi_present, match_hoff;  // per-call scratch of
+  std::vector<int32_t> twi_ids;                                          // transfer_with_insert / match
 };
 
 namespace {
@@ -587,6 +589,42 @@ int run_copy(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *
   const int32_t *d_src = nullptr, *d_dst = nullptr;
   const bool direct = (flags & MP_DIRECT) != 0;
   bool dst_ascends = false;
+
+  // A transfer of one request (a few dozen blocks) between HBM pools: the ids, sorted by
+  // destination, travel in the kernel arguments -- no table upload, no event, one launch
+  // (fused) or two (through one staging round).
+  if (!(flags & MP_PER_FRAGMENT) && s_hbm && d_hbm && small_copy_possible(n, planes, x->F, tune) &&
+      (direct || (uint64_t)n * B <= x->desc.staging_bytes)) {
+    uint64_t keys[kSmallTable];
+    for (uint32_t i = 0; i < n; ++i)
+      keys[i] = ((uint64_t)(uint32_t)dst_ids[i] << 32) | (uint32_t)src_ids[i];
+    std::sort(keys, keys + n);
+    SmallTables ids;
+    for (uint32_t i = 0; i < n; ++i) {
+      ids.dst[i] = (int32_t)(uint32_t)(keys[i] >> 32);
+      ids.src[i] = (int32_t)(uint32_t)keys[i];
+    }
+    const CopySide from = pool_side(src, nullptr, l0), to = pool_side(dst, nullptr, l0, true);
+    if (direct) {
+      ProfScope ps(x, kProfDirect, 2ull * n * B);
+      HIP_TRY(x, launch_block_copy_small(from, to, ids, true, true, n, planes, x->F, tune, d.n_cus,
+                                         d.stream));
+      return MP_OK;
+    }
+    const CopySide records = record_side(x, x->desc.staging, planes);
+    {
+      ProfScope ps(x, kProfGather, 2ull * n * B);
+      HIP_TRY(x, launch_block_copy_small(from, records, ids, true, false, n, planes, x->F, tune,
+                                         d.n_cus, d.stream));
+    }
+    {
+      ProfScope ps(x, kProfScatter, 2ull * n * B);
+      HIP_TRY(x, launch_block_copy_small(records, to, ids, false, true, n, planes, x->F, tune,
+                                         d.n_cus, d.stream));
+    }
+    return MP_OK;
+  }
+
   if (!(flags & MP_PER_FRAGMENT)) {
     // The pair of tables is sorted before it goes up (the result does not depend on the order
     // of the entries): by destination id, so that the stores of a launch sweep each plane of
@@ -790,35 +828,43 @@ int twi_core(mp_pool *src, mp_pool *dst, const uint32_t *tokens, const uint32_t 
   if ((rc = check_same_pool(src, dst, src_blocks, dst_blocks, total, flags)) != MP_OK) return rc;
 
   // the receiver hashes the prompts (device kernel)
-  std::vector<uint32_t> hoff;
+  std::vector<uint32_t> &hoff = dst->twi_hoff;  // pool-owned scratch: no allocation per call
   const uint32_t *htok = nullptr;
   const uint64_t *hh = nullptr;
   rc = device_hashes(dst, tokens, tok_off, n_req, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok,
                      &hh);
   if (rc != MP_OK) return rc;
 
-  // blocks [0, first_block) must already be indexed at the receiver
-  std::vector<std::vector<int32_t>> ids(n_req);
-  std::vector<uint32_t> present(n_req, 0);
+  // blocks [0, first_block) must already be indexed at the receiver.  ids of request r:
+  // ids[ids_off[r] ..), one per prompt block (and per table entry beyond the full blocks)
+  std::vector<int32_t> &ids = dst->twi_ids;
+  std::vector<uint32_t> &ids_off = dst->twi_ids_off, &present = dst->twi_present;
+  ids_off.resize(n_req + 1);
+  present.resize(n_req);
+  ids_off[0] = 0;
   for (uint32_t r = 0; r < n_req; ++r) {
     const uint32_t nb = hoff[r + 1] - hoff[r], n = blk_off[r + 1] - blk_off[r];
-    ids[r].assign(std::max(nb, first_block[r] + n), kNoBlock);
-    present[r] = dst->idx.walk(htok + tok_off[r], hh + hoff[r], nb, ids[r].data());
+    ids_off[r + 1] = ids_off[r] + std::max(nb, first_block[r] + n);
+  }
+  ids.assign(ids_off[n_req], kNoBlock);
+  for (uint32_t r = 0; r < n_req; ++r) {
+    present[r] = dst->idx.walk(htok + tok_off[r], hh + hoff[r], hoff[r + 1] - hoff[r],
+                               ids.data() + ids_off[r]);
     if (present[r] < first_block[r])
       return fail(src, MP_ESTALE, "claimed prefix is not in the destination index");
   }
   if (flags & MP_DST_GIVEN) {
     if (n_req != 1) return fail(src, MP_EINVAL, "MP_DST_GIVEN is not supported in batched form");
-    for (uint32_t i = 0; i < total; ++i) ids[0][first_block[0] + i] = dst_blocks[i];
-    if (!dst->idx.adoptable(ids[0].data(), present[0], hoff[1]))
+    for (uint32_t i = 0; i < total; ++i) ids[first_block[0] + i] = dst_blocks[i];
+    if (!dst->idx.adoptable(ids.data(), present[0], hoff[1]))
       return fail(src, MP_EINVAL, "a given destination block is already indexed");
   }
   // allocation step, with the matched prefixes protected from on-demand eviction
   for (uint32_t r = 0; r < n_req; ++r)
-    for (uint32_t i = 0; i < first_block[r]; ++i) dst->idx.pin(ids[r][i]);
+    for (uint32_t i = 0; i < first_block[r]; ++i) dst->idx.pin(ids[ids_off[r] + i]);
   auto unpin_all = [&]() {
     for (uint32_t r = 0; r < n_req; ++r)
-      for (uint32_t i = 0; i < first_block[r]; ++i) dst->idx.unpin(ids[r][i]);
+      for (uint32_t i = 0; i < first_block[r]; ++i) dst->idx.unpin(ids[ids_off[r] + i]);
   };
   if (!(flags & MP_DST_GIVEN)) {
     if (!dst->idx.alloc(total, dst_blocks, (flags & MP_EVICT_ON_DEMAND) != 0)) {
@@ -827,7 +873,7 @@ int twi_core(mp_pool *src, mp_pool *dst, const uint32_t *tokens, const uint32_t 
     }
     for (uint32_t r = 0; r < n_req; ++r)
       for (uint32_t i = 0; i < blk_off[r + 1] - blk_off[r]; ++i)
-        ids[r][first_block[r] + i] = dst_blocks[blk_off[r] + i];
+        ids[ids_off[r] + first_block[r] + i] = dst_blocks[blk_off[r] + i];
   }
 
   // transmission step
@@ -841,7 +887,7 @@ int twi_core(mp_pool *src, mp_pool *dst, const uint32_t *tokens, const uint32_t 
 
   // insertion step: only after all data is in place (or ordered behind it on the stream)
   for (uint32_t r = 0; r < n_req; ++r)
-    dst->idx.insert(htok + tok_off[r], hh + hoff[r], hoff[r + 1] - hoff[r], ids[r].data());
+    dst->idx.insert(htok + tok_off[r], hh + hoff[r], hoff[r + 1] - hoff[r], ids.data() + ids_off[r]);
   unpin_all();
   if (dst->cb) dst->cb(dst->cb_user, priv, priv_len, dst_blocks, total);
   return MP_OK;
@@ -1161,7 +1207,7 @@ int mp_match_batch(mp_pool_t *p, const uint32_t *tokens, const uint32_t *tok_off
         return fail(p, MP_EINVAL, "offsets must be non-decreasing");
     if (!tokens && tok_off[n_req]) return fail(p, MP_EINVAL, "null tokens");
     if (!blocks_out && blk_off[n_req] != blk_off[0]) return fail(p, MP_EINVAL, "null output array");
-    std::vector<uint32_t> hoff;
+    std::vector<uint32_t> &hoff = p->match_hoff;
     const uint32_t *htok;
     const uint64_t *hh;
     if (p->dev.mirror_on && n_req) {

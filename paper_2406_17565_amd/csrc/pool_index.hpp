@@ -150,7 +150,11 @@ class PoolIndex {
   bool alloc(uint32_t n, int32_t *out, bool may_evict) {
     uint32_t nfree = n_free();
     if (nfree < n) {
-      if (!may_evict || nfree + evictable_total() < n) return false;
+      if (!may_evict) return false;
+      // Every current unreferenced leaf can go, and an eviction removes at most one leaf from
+      // that set (it may add the parent), so `shortfall` leaves at hand are enough; only
+      // otherwise is the whole index counted.
+      if (lru_.size() < n - nfree && nfree + evictable_total() < n) return false;
       evict(n - nfree);
     }
     for (uint32_t i = 0; i < n; ++i) {
