@@ -198,6 +198,16 @@ uint32_t do_insert(orc_pool *p, const uint32_t *tokens, uint32_t nb, const int32
   return created;
 }
 
+// A transfer inside ONE pool reads its source blocks after the allocation step (section 4.3:
+// allocation, then transmission), so the sources are in use for the whole call: they carry a
+// reference while the destination blocks are found, and on-demand eviction cannot take a
+// historical source block away (and hand it back as a destination).  Between two pools the
+// source pool is not touched by the allocation, and nothing needs holding.
+void hold_sources(orc_pool *src, const orc_pool *dst, const int32_t *ids, uint32_t n, int delta) {
+  if (src != dst) return;
+  for (uint32_t i = 0; i < n; ++i) src->ref[ids[i]] += delta;
+}
+
 void copy_all(const orc_pool *src, orc_pool *dst, const int32_t *s, const int32_t *d, uint32_t n) {
   std::vector<uint8_t> staging((size_t)n * src->B);
   orc_gather(src, s, n, staging.data());
@@ -299,7 +309,7 @@ void orc_stats(const orc_pool_t *p, uint32_t *n_free, uint32_t *n_held, uint32_t
   *n_held = held; *n_indexed = idx; *n_historical = hist; *clock = p->clock;
 }
 
-// alloc_mem (Table 1: "alloc a certain type of memory ..., return addrList"); the table's
+// alloc_mem (Table 1: hands out blocks of the pool's memory type as an address list); the table's
 // caption allows on-demand allocation, here: eviction of the shortfall when the flag asks.
 int orc_alloc(orc_pool_t *p, uint32_t n, int32_t *out, uint32_t flags) {
   if (!p || (!out && n)) return ORC_EINVAL;
@@ -322,7 +332,7 @@ int orc_free(orc_pool_t *p, const int32_t *blocks, uint32_t n) {
   return ORC_OK;
 }
 
-// insert (Table 1: "insert prompt token and KV cache address mapping into local index");
+// insert (Table 1: records, in the local index, which blocks hold the KV of the prompt's tokens);
 // granularity = the engine's block (section 4.2, last paragraph).
 int orc_insert(orc_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, const int32_t *blocks,
                uint32_t n_blocks, uint32_t *n_new) {
@@ -336,7 +346,7 @@ int orc_insert(orc_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, const i
   return ORC_OK;
 }
 
-// match (Table 1: "find prompt's cached data if any, return addrList"): the longest indexed
+// match (Table 1: returns the addresses of the prompt's cached KV, if there is any): the longest indexed
 // block-aligned prefix.
 int orc_match(orc_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, int32_t *blocks_out,
               uint32_t cap, uint32_t *n_matched, uint32_t flags) {
@@ -354,7 +364,7 @@ int orc_match(orc_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, int32_t 
   return ORC_OK;
 }
 
-// delete (Table 1: "delete prompt's cached data if any").  The paper says no more; reading:
+// delete (Table 1: drops the prompt's cached KV, if there is any).  The paper says no more; reading:
 // the prompt's own blocks go, shared or referenced ones stay -- from the deepest matched node
 // upwards, remove nodes while they are unreferenced leaves.
 int orc_delete(orc_pool_t *p, const uint32_t *tokens, uint32_t n_tokens, uint32_t *n_deleted) {
@@ -413,7 +423,9 @@ int orc_transfer(orc_pool_t *src, orc_pool_t *dst, const int32_t *src_blocks,
   if (flags & ORC_DST_GIVEN) {
     rc = check_given_dst_ids(dst, dst_blocks, n);
   } else {
+    hold_sources(src, dst, src_blocks, n, +1);
     rc = alloc_blocks(dst, n, dst_blocks, flags);
+    hold_sources(src, dst, src_blocks, n, -1);
   }
   if (rc != ORC_OK) return rc;
   copy_all(src, dst, src_blocks, dst_blocks, n);
@@ -480,7 +492,9 @@ int orc_transfer_with_insert(orc_pool_t *src, orc_pool_t *dst, const uint32_t *t
   // keep the matched prefix safe from on-demand eviction while this call runs
   for (uint32_t i = 0; i < first_block; ++i) ++dst->ref[path[i]->block];
   if (!(flags & ORC_DST_GIVEN)) {
+    hold_sources(src, dst, src_blocks, n, +1);
     rc = alloc_blocks(dst, n, dst_blocks, flags);
+    hold_sources(src, dst, src_blocks, n, -1);
     if (rc != ORC_OK) {
       for (uint32_t i = 0; i < first_block; ++i) --dst->ref[path[i]->block];
       return rc;
@@ -520,7 +534,9 @@ int orc_transfer_with_insert_batch(orc_pool_t *src, orc_pool_t *dst, const uint3
     if (prefix[r].size() < first_block[r]) return ORC_ESTALE;
   }
   for (auto &pr : prefix) for (Node *nd : pr) ++dst->ref[nd->block];
+  hold_sources(src, dst, src_blocks, total, +1);
   rc = alloc_blocks(dst, total, dst_blocks, flags);
+  hold_sources(src, dst, src_blocks, total, -1);
   if (rc == ORC_OK) {
     copy_all(src, dst, src_blocks, dst_blocks, total);
     for (uint32_t r = 0; r < n_req; ++r) {

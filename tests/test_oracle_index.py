@@ -280,6 +280,51 @@ def test_transfer_with_insert_protects_its_prefix_from_eviction():
     assert dst.stats()["n_held"] == 3              # the temporary pins are gone
 
 
+def test_in_pool_transfer_holds_its_sources_while_it_allocates():
+    """A transfer inside one pool (section 4.3: allocation first, transmission second) reads its
+    sources after the destination blocks were found, so on-demand eviction must not take a
+    historical SOURCE block -- else the block would come back as its own destination and its
+    index entry would be lost.  Derived by hand from the rules: LRU leaf eviction, LIFO free
+    list, sources referenced for the duration of the allocation."""
+    A = np.arange(100, 100 + BS, dtype=np.uint32)           # two one-block prompts, cached and
+    Bq = np.arange(200, 200 + BS, dtype=np.uint32)          # unreferenced (historical)
+    p = pool(4, seed=3)
+    for t in (A, Bq):
+        rc, ids = p.alloc(1)
+        assert rc == 0 and p.insert(t, ids) == (0, 1) and p.free(ids) == 0
+    rc, held = p.alloc(2)                                    # the pool is full: 0,1 historical, 2,3 held
+    assert rc == 0 and held.tolist() == [2, 3]
+    before = p.data.copy()
+    # both historical blocks are sources: nothing may be evicted, the call fails and changes nothing
+    rc, _ = O.transfer(p, p, [0, 1], flags=O.EVICT_ON_DEMAND)
+    assert rc == O.ENOMEM
+    assert np.array_equal(p.data, before) and p.stats()["n_historical"] == 2
+    assert p.match(A)[1].tolist() == [0] and p.match(Bq)[1].tolist() == [1]
+    # one source: the OTHER historical block is the victim although the source is the older one
+    rc, d = O.transfer(p, p, [0], flags=O.EVICT_ON_DEMAND)
+    assert rc == 0 and d.tolist() == [1]
+    F = p.F
+    view = p.data.reshape(2 * GEOM[0], 4, F)
+    assert np.array_equal(view[:, 1], before.reshape(2 * GEOM[0], 4, F)[:, 0])   # block 0 copied into 1
+    assert p.match(A)[1].tolist() == [0] and p.match(Bq)[1].size == 0           # A survived, Bq was evicted
+    assert p.stats()["n_held"] == 3 and p.free(d) == 0
+    # the same through transfer_with_insert inside one pool
+    q = pool(4, seed=4)
+    for t in (A, Bq):
+        rc, ids = q.alloc(1)
+        assert q.insert(t, ids) == (0, 1) and q.free(ids) == 0
+    q.alloc(2)
+    C = np.arange(300, 300 + BS, dtype=np.uint32)
+    rc, d = O.transfer_with_insert(q, q, C, 0, [0], flags=O.EVICT_ON_DEMAND)
+    assert rc == 0 and d.tolist() == [1] and q.match(A)[1].tolist() == [0] and q.match(C)[1].tolist() == [1]
+    # between two pools nothing is held: the source pool's references are untouched
+    r1, r2 = pool(4, seed=5), pool(4, seed=6)
+    rc, ids = r1.alloc(1)
+    assert r1.insert(A, ids) == (0, 1) and r1.free(ids) == 0
+    rc, d = O.transfer(r1, r2, [0], flags=O.EVICT_ON_DEMAND)
+    assert rc == 0 and r1.stats()["n_held"] == 0 and r1.stats()["n_historical"] == 1
+
+
 def test_batch_form():
     rng = np.random.default_rng(6)
     src, dst = _two_pools()
