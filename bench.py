@@ -183,6 +183,44 @@ def cpu_baseline(W, geom, n_sessions=64, n_turns=4, NB_src=4096, NB_dst=8704):
                             "what": "chained block hashes of every prompt + trie walk (match)"})
 
 
+def per_request_c(mode, timed_sets=3):
+    """Builds bench_per_request.c with gcc and runs it: the per-request flavour of the path from
+    plain C, so the library's own time per request is seen without Python around it."""
+    import shutil
+    import subprocess
+    import tempfile
+    from paper_2406_17565_amd import build as B
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        return {"error": "gcc not found"}
+    libdir, hip = os.path.dirname(B.LIB), "/opt/rocm/lib"
+    with tempfile.TemporaryDirectory() as tmp:
+        exe = os.path.join(tmp, "bench_per_request")
+        cmd = [gcc, "-O2", "-std=c99", "-I", os.path.join(ROOT, "include"),
+               os.path.join(ROOT, "bench_per_request.c"), "-o", exe, "-L", libdir, "-lmempool", "-L", hip,
+               "-lamdhip64", f"-Wl,-rpath,{libdir}", f"-Wl,-rpath,{hip}"]
+        try:
+            subprocess.check_call(cmd)
+            out = subprocess.run([exe, mode, str(timed_sets)], capture_output=True, text=True, timeout=300)
+        except (subprocess.CalledProcessError, subprocess.TimeoutExpired, OSError) as e:
+            return {"error": str(e)[:200]}
+        if out.returncode != 0:
+            return {"error": (out.stderr or out.stdout)[-300:]}
+        res = json.loads(out.stdout.strip().splitlines()[-1])
+        res.pop("what", None)
+        return res
+
+
+def hash_floor_us(turn, bs, clock_hz=2.4e9, pcie_bytes_per_s=64e9):
+    """What the hash kernel cannot beat on one batch: the serial chain of the longest prompt (25
+    dependent scalar instructions per step, and a lone wave issues one instruction every four
+    cycles), and fetching the host-resident tokens over the host link."""
+    nblk = (turn["tok_off"][1:] - turn["tok_off"][:-1]) // bs
+    chain = float(nblk.max()) * 25 * 4 / clock_hz * 1e6
+    fetch = 4.0 * float(turn["tok_off"][-1]) / pcie_bytes_per_s * 1e6
+    return chain, fetch
+
+
 def host_tier(args):
     """Config 5's variant: HBM pool -> pinned-host pool (gather kernel, then device-to-host
     copies of records on the side stream) and back (host-to-device, then scatter kernel).
@@ -447,6 +485,7 @@ def main():
     ap.add_argument("--per-fragment", action="store_true",
                     help="reference point: one copy call per discrete fragment vs one launch")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-per-request", action="store_true", help="skip the per-request figures (C helper + binding)")
     ap.add_argument("--tune", default="", help="comma list key=value for mp_set_tunable")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -564,6 +603,7 @@ def main():
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     step_ms = sorted(marks[k].elapsed_time(marks[k + 1]) for k in range(args.steps))
+    _, h_ms, h_n, h_bytes = M.mp_profile_read(dst.h, M.PROF_HASH)      # hash launches of the timed steps
 
     # match on its own: the batches of the last two steps are fully indexed at the destination,
     # so every block is hashed (kernel) and probed (host).  Two batches alternate because the
@@ -600,8 +640,28 @@ def main():
         rc, ms, n, nbytes = M.mp_profile_read(src.h, kind)
         per_kind[kind] = (ms, n, nbytes)
         k_ms, k_n, k_bytes = k_ms + ms, k_n + n, k_bytes + nbytes
-    _, h_ms, h_n, h_bytes = M.mp_profile_read(dst.h, M.PROF_HASH)
+    _, sh_ms, sh_n, _ = M.mp_profile_read(dst.h, M.PROF_HASH)          # those of the stand-alone matches
     achieved = k_bytes / (k_ms * 1e-3) / 1e9 if k_ms else 0.0
+    floors = [hash_floor_us(b, bs) for b in pair]
+    chain_floor = sum(f[0] for f in floors) / len(floors)
+    fetch_floor = sum(f[1] for f in floors) / len(floors)
+    hash_us = sh_ms / sh_n * 1e3 if sh_n else None
+    roofline_hash = {
+        "bound": "latency",
+        "kernel": "block_hash_kernel",
+        "unit": "us per launch",
+        "achieved": round(hash_us, 2) if hash_us else None,
+        "peak": round(max(chain_floor, fetch_floor), 2),
+        "frac": round(max(chain_floor, fetch_floor) / hash_us, 4) if hash_us else None,
+        "chain_floor_us": round(chain_floor, 2),
+        "token_fetch_floor_us": round(fetch_floor, 2),
+        "launches": sh_n,
+        "blocks_per_launch": last_blocks,
+        "what": "stand-alone mp_match_batch of fully indexed batches; achieved = mean launch duration by HIP "
+                "events on the destination stream (the events themselves add a few us to a launch this short); "
+                "peak = the floor no schedule can beat: max(serial chain of the longest prompt at 25 dependent "
+                "scalar instructions x 4 cycles per step at 2.4 GHz, host-resident tokens at 64 GB/s over the host link)",
+    }
 
     # the same workload once more with the fused pool-to-pool kernel (half the HBM traffic), as a
     # second figure next to the headline; not part of the timed K steps above
@@ -698,7 +758,9 @@ def main():
                   "standalone_batch_us": round(sum(m_ts) / len(m_ts) * 1e6, 1),
                   "blocks_per_batch": last_blocks,
                   "inside_pipelined_steps_blocks_per_s": round(hashed / dt, 1)},
-        "hash_kernel": {"launches": h_n, "avg_us": round(h_ms / h_n * 1e3, 2) if h_n else None},
+        "hash_kernel": {"launches": h_n, "avg_us": round(h_ms / h_n * 1e3, 2) if h_n else None,
+                        "where": "inside the timed steps"},
+        "roofline_hash": roofline_hash,
         "roofline": {
             "bound": "hbm",
             "achieved": round(achieved, 1),
@@ -721,6 +783,39 @@ def main():
     }
     if fused:
         out["fused"] = fused
+    if args.config == 3 and not (args.direct or args.per_request or args.by_layer or args.no_per_request):
+        # (A) one call per session, next to (B) the batched call per turn that `value` is: the same
+        # workload with mp_match + mp_transfer_with_insert per request, from plain C (the library's
+        # own time) and through this Python binding (ctypes + numpy on top)
+        for ids in state["held"]:
+            assert M.mp_free(dst.h, ids) == 0
+        state["held"].clear()
+        per_request = {"c_abi": {"staged": per_request_c("staged"), "direct": per_request_c("direct")},
+                       "python_binding": {}}
+        for j, (name, fl) in enumerate((("staged", flags), ("direct", flags | M.MP_DIRECT))):
+            eps = [build_epoch(W, geom, 3, 100 + 2 * j + k) for k in range(2)]   # fresh prompts per flavour
+            n_req = mv = 0
+            for k, ep in enumerate(eps):                       # the first set of sessions warms up
+                if k == 1:
+                    torch.cuda.synchronize()
+                    t1 = time.perf_counter()
+                for turn in ep:
+                    got = run_step_per_request(M, src, dst, turn, rng.permutation(NB_src).astype(np.int32),
+                                               state, fl)
+                    if k == 1:
+                        mv += got
+                        n_req += len(turn["nblk"])
+                for ids in state["held"]:
+                    assert M.mp_free(dst.h, ids) == 0
+                state["held"].clear()
+            torch.cuda.synchronize()
+            t_pr = time.perf_counter() - t1
+            per_request["python_binding"][name] = {"requests": n_req, "us_per_request": round(t_pr / n_req * 1e6, 2),
+                                                   "GBs": round(mv * geom.B / t_pr / 1e9, 1)}
+        per_request["what"] = ("config 3, one mp_match + one asynchronous mp_transfer_with_insert per request "
+                               "(24-50 blocks = 48-100 MiB each); us_per_request = wall time / requests, "
+                               "device synchronisation at the end included")
+        out["per_request"] = per_request
     if not args.no_cpu_baseline and args.config == 3:
         out["cpu_baseline"] = cpu_baseline(W, geom)
     print(json.dumps(out))

@@ -163,6 +163,10 @@ int mp_evict(mp_pool_t *p, uint32_t n_blocks, uint32_t *n_evicted_out);
  *           that loads straight from the mapped host pool).  host->host is not supported.
  * Transfers larger than the staging buffer are cut into staging-sized rounds.
  * src ids must be held or historical; given dst ids must be held and duplicate-free.
+ * Inside ONE pool (src == dst) the source blocks are held while the destination blocks are
+ * allocated, so MP_EVICT_ON_DEMAND never evicts what the call is about to copy.
+ * The entries may be copied in any order (the library sorts the pair of tables by destination
+ * id before the launch); dst_blocks comes back in the caller's order.
  * priv / priv_len: opaque user data handed to the receiver callback, never sent to the GPU. */
 int mp_transfer(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks,
                 int32_t *dst_blocks /* in with MP_DST_GIVEN, else out */, uint32_t n,
@@ -175,8 +179,8 @@ int mp_transfer_batch(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks,
                       int32_t *dst_blocks, const uint32_t *blk_off, uint32_t n_req,
                       uint32_t flags);
 
-/* By-layer transfer (section 4.3: an explicit destination list "is particularly useful for
- * constructing layer-by-layer transmissions"; section 5.2: by-layer vs by-request): copies only
+/* By-layer transfer (section 4.3 names layer-by-layer transmission as the use of an explicit
+ * destination list; section 5.2 compares by-layer with by-request): copies only
  * layers [layer_begin, layer_end) of every listed block, so an engine can ship a layer as soon
  * as its prefill finished.  The destination ids are always given (allocate them once with
  * mp_alloc before the first layer; insert with mp_insert after the last).  Staging holds packed
@@ -208,7 +212,7 @@ int mp_transfer_with_insert_batch(mp_pool_t *src, mp_pool_t *dst, const uint32_t
                                   const uint32_t *blk_off /* n_req+1 into both tables */,
                                   uint32_t flags);
 
-/* swap_out (Table 1: "swap a given number of blocks from HBM to DRAM"; section 4.2: index
+/* swap_out (Table 1: moves a given number of blocks from HBM down to DRAM; section 4.2: index
  * nodes may point to HBM or DRAM).  `upper` and `lower` are two pools of one instance (same
  * geometry and hash_seed, else MP_ESHAPE / MP_EINVAL), normally an HBM pool and a pinned-host
  * pool.  Up to num_blocks times: take the block mp_evict(upper) would take next (least recently
@@ -227,8 +231,8 @@ int mp_transfer_with_insert_batch(mp_pool_t *src, mp_pool_t *dst, const uint32_t
 int mp_swap_out(mp_pool_t *upper, mp_pool_t *lower, uint32_t num_blocks, uint32_t flags,
                 uint32_t *n_swapped_out);
 
-/* swap_in (Table 1: "swap blocks with given address from DRAM to HBM"; section 8.3: historical
- * KV that sits in DRAM is swapped into HBM before prefill uses it).  lower_blocks: n ids that
+/* swap_in (Table 1: brings the blocks at the given addresses from DRAM up to HBM; section 8.3:
+ * historical KV that sits in DRAM is swapped into HBM before prefill uses it).  lower_blocks: n ids that
  * are indexed in `lower` (what mp_match(lower) returned).  The call is one use of the lower
  * tier (one clock tick).  For every id, deepest prefix first (ties: list order): unless the id
  * lies on a prefix handled earlier in the same call, its path is touched in `lower` and the
@@ -286,8 +290,12 @@ int mp_match_hashed(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens,
 int mp_delete_hashed(mp_pool_t *p, const uint32_t *tokens, uint32_t n_tokens,
                      const uint64_t *hashes, uint32_t *n_deleted_out);
 
-/* Data-plane pieces of a transfer, exposed for tests and measurement.  `tbl` are HOST arrays
- * of n block ids; `staging` of the pool is the other end. */
+/* The two data-plane steps of a transfer on their own (section 5.2: the 2*L discrete fragments
+ * of a block <-> one aggregated record), exposed for tests and measurement.  mp_gather copies
+ * block tbl[i] of the pool into record i of the pool's staging buffer; mp_scatter copies record
+ * i into block tbl[i] (ids distinct).  `tbl`: HOST array of n ids; n records must fit the
+ * staging buffer (MP_ENOSTAGING).  The record order is the table order (nothing is sorted).
+ * With MP_ASYNC the work is only enqueued on the pool's stream. */
 int mp_gather(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags);
 int mp_scatter(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags);
 

@@ -769,7 +769,8 @@ int finish_copy(mp_pool *src, mp_pool *dst, uint32_t flags) {
 // A transfer inside one pool with an explicit destination list may read and write the same
 // blocks.  The staged path is defined as "gather everything, then scatter", which holds only
 // if the whole table fits one staging round; the fused path cannot honour it at all.
-// (Freshly allocated destination ids never overlap held sources.)
+// (Freshly allocated destination ids never overlap the sources: the sources are held while
+// the destination blocks are allocated.)
 int check_same_pool(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const int32_t *dst_ids,
                     uint32_t n, uint32_t flags) {
   if (src != dst || !(flags & MP_DST_GIVEN) || n == 0) return MP_OK;
@@ -779,6 +780,17 @@ int check_same_pool(mp_pool *src, mp_pool *dst, const int32_t *src_ids, const in
   if ((uint64_t)n * src->B > src->desc.staging_bytes)
     return fail(src, MP_ENOSTAGING, "overlapping in-pool transfer must fit the staging buffer");
   return MP_OK;
+}
+
+// The sources of a transfer inside one pool are read after the allocation step, so they are
+// held (one reference each) while destination blocks are found: on-demand eviction then cannot
+// take a historical source block and hand it back as its own destination.
+void hold_sources(mp_pool *src, mp_pool *dst, const int32_t *ids, uint32_t n, bool hold) {
+  if (src != dst) return;
+  for (uint32_t i = 0; i < n; ++i) {
+    if (hold) src->idx.pin(ids[i]);
+    else src->idx.unpin(ids[i]);
+  }
 }
 
 int check_src_ids(mp_pool *src, const int32_t *ids, uint32_t n) {
@@ -867,7 +879,10 @@ int twi_core(mp_pool *src, mp_pool *dst, const uint32_t *tokens, const uint32_t 
       for (uint32_t i = 0; i < first_block[r]; ++i) dst->idx.unpin(ids[ids_off[r] + i]);
   };
   if (!(flags & MP_DST_GIVEN)) {
-    if (!dst->idx.alloc(total, dst_blocks, (flags & MP_EVICT_ON_DEMAND) != 0)) {
+    hold_sources(src, dst, src_blocks, total, true);
+    const bool got = dst->idx.alloc(total, dst_blocks, (flags & MP_EVICT_ON_DEMAND) != 0);
+    hold_sources(src, dst, src_blocks, total, false);
+    if (!got) {
       unpin_all();
       return fail(src, MP_ENOMEM, "destination pool cannot supply the blocks");
     }
@@ -1312,9 +1327,12 @@ int mp_transfer(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks, int32
       return fail(src, MP_EINVAL, "given destination ids must be held and distinct");
     if ((rc = check_copy_feasible(src, dst, n, flags)) != MP_OK) return rc;
     if ((rc = check_same_pool(src, dst, src_blocks, dst_blocks, n, flags)) != MP_OK) return rc;
-    if (!(flags & MP_DST_GIVEN) &&
-        !dst->idx.alloc(n, dst_blocks, (flags & MP_EVICT_ON_DEMAND) != 0))
-      return fail(src, MP_ENOMEM, "destination pool cannot supply the blocks");
+    if (!(flags & MP_DST_GIVEN)) {
+      hold_sources(src, dst, src_blocks, n, true);
+      const bool got = dst->idx.alloc(n, dst_blocks, (flags & MP_EVICT_ON_DEMAND) != 0);
+      hold_sources(src, dst, src_blocks, n, false);
+      if (!got) return fail(src, MP_ENOMEM, "destination pool cannot supply the blocks");
+    }
     rc = run_copy(src, dst, src_blocks, dst_blocks, n, flags);
     if (rc == MP_OK) rc = finish_copy(src, dst, flags);
     if (rc != MP_OK) {  // a HIP failure: hand the fresh destination blocks back

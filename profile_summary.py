@@ -76,6 +76,10 @@ def cmd_stats(a):
     if a.bench_json:
         b = json.load(open(a.bench_json))
         rf = b["roofline"]
+        if "avg_launch_us" not in rf:          # a side mode of bench.py (host tier, ...): quote its line as it is
+            L += ["", "bench.py's line in the same run: " + json.dumps({k: v for k, v in b.items() if k != "config"})]
+            write(a.out, L)
+            return
         L += ["", f"bench.py's own HIP-event timing in the same run: {rf['kernel']} avg {rf['avg_launch_us']} us over "
                   f"{rf['launches']} timed launches (the trace also counts warm-up launches and the extra legs);",
               f"algorithmic bytes per launch {rf['alg_bytes_per_launch']} => {rf['achieved']} GB/s = "

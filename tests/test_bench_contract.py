@@ -36,3 +36,11 @@ def test_default_mode_prints_one_json_line():
     assert abs(rf["frac"] - rf["achieved"] / rf["peak"]) < 1e-3
     assert 0.3 < rf["frac"] < 1.0            # a copy cannot beat the HBM roofline
     assert d["value"] > 0 and d["ms_per_step"] > 0
+    assert 0 < d["min_ms"] <= d["median_ms"] <= d["max_ms"]
+    rh = d["roofline_hash"]
+    assert rh["bound"] == "latency" and 0 < rh["frac"] <= 1.0 and rh["peak"] <= rh["achieved"]
+    pr = d["per_request"]
+    for path in ("staged", "direct"):                  # (A) one call per request, from C and from Python
+        assert pr["c_abi"][path].get("us_per_request", 0) > 0, pr["c_abi"][path]
+        assert pr["python_binding"][path]["us_per_request"] > 0
+    assert d["fused"]["value"] > d["value"]            # half the traffic per block

@@ -264,6 +264,42 @@ def test_transfer_inside_one_pool(gpu):
     g.close()
 
 
+@pytest.mark.parametrize("direct", [0, 1])
+def test_in_pool_transfer_never_evicts_its_sources(gpu, direct):
+    """Inside one pool the sources are held while destination blocks are allocated: with
+    on-demand eviction a historical source block is never the victim (it would come back as its
+    own destination).  Same calls on the oracle, whole state compared."""
+    M, TorchPool = gpu
+    geom = GEOMS["f480"]
+    bs = geom[3]
+    fl = M.MP_EVICT_ON_DEMAND | (M.MP_DIRECT if direct else 0)
+    o, g = make_pair(gpu, geom, 10, 21, staging_blocks=2)
+    rng = np.random.default_rng(22)
+    prompts = [rng.integers(0, 1000, bs * k, dtype=np.uint32) for k in (1, 1, 2, 3)]
+    for t in prompts:                                   # 7 cached, unreferenced blocks
+        rc, ids = M.mp_alloc(g.h, len(t) // bs)
+        assert rc == 0 and ids.tolist() == o.alloc(len(t) // bs)[1].tolist()
+        assert M.mp_insert(g.h, t, ids) == o.insert(t, ids) and M.mp_free(g.h, ids) == o.free(ids) == 0
+    rc, held = M.mp_alloc(g.h, 3)                       # the pool is full
+    assert rc == 0 and held.tolist() == o.alloc(3)[1].tolist()
+    for src_tbl in ([0], [1, 0], [2, 3, 0], [4, 5, 6, 1], [0, 1, 2, 3, 4, 5, 6]):
+        rc, d = M.mp_transfer(g.h, g.h, src_tbl, flags=fl)
+        rco, d_o = O.transfer(o, o, src_tbl, flags=O.EVICT_ON_DEMAND)
+        assert rc == rco, (src_tbl, M.mp_last_error(g.h))
+        if rc == 0:
+            assert d.tolist() == d_o.tolist() and not set(d.tolist()) & set(src_tbl)
+            assert M.mp_free(g.h, d) == o.free(d_o) == 0
+        _same_state(o, g)
+    t = rng.integers(0, 1000, 2 * bs, dtype=np.uint32)
+    rc, d = M.mp_transfer_with_insert(g.h, g.h, t, 0, [0, 2], flags=fl)
+    rco, d_o = O.transfer_with_insert(o, o, t, 0, [0, 2], flags=O.EVICT_ON_DEMAND)
+    assert rc == rco and d.tolist() == d_o.tolist()
+    _same_state(o, g)
+    for p in prompts + [t]:
+        assert M.mp_match(g.h, p, 4)[1].tolist() == o.match(p)[1].tolist()
+    g.close()
+
+
 def test_tiny_config_walkthrough(gpu):
     """Config 1: match, transfer_with_insert of the unmatched suffix, match again."""
     M, TorchPool = gpu
