@@ -331,8 +331,9 @@ int mp_set_tunable(mp_pool_t *p, const char *key, int value);
  * the GPU at hand; its hardware-counter readings scale those of the real kernels. */
 int mp_plain_copy(void *dst, const void *src, uint64_t bytes, void *stream, double *ms_out);
 
-/* Host-only self check of internal integer arithmetic (multiply-shift division used for
- * work-item decomposition).  Returns MP_OK or MP_EINVAL. */
+/* Host-only self check of internal integer work: the multiply-shift division used for the
+ * work-item decomposition, and the sort of table pairs (both of its code paths).  Returns
+ * MP_OK or MP_EINVAL. */
 int mp_selftest(void);
 
 #ifdef __cplusplus

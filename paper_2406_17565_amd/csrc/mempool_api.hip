@@ -443,9 +443,9 @@ int launch_probe(mp_pool *p, const uint32_t *k_tok, uint32_t n_req, const uint32
 // Orders the table pair by one side's ids (results do not depend on the order of the entries;
 // destination ids are distinct).  Keys are (id << 32 | other id); small tables use std::sort,
 // large ones an LSD radix sort over the id bits, so the cost stays a few ns per entry.
-void sort_pairs(mp_pool *x, const int32_t *key_ids, const int32_t *other_ids, uint32_t n,
-                uint32_t key_range, int32_t *key_out, int32_t *other_out) {
-  std::vector<uint64_t> &a = x->sort_a, &b = x->sort_b;
+void sort_pairs(std::vector<uint64_t> &a, std::vector<uint64_t> &b, const int32_t *key_ids,
+                const int32_t *other_ids, uint32_t n, uint32_t key_range, int32_t *key_out,
+                int32_t *other_out) {
   a.resize(n);
   for (uint32_t i = 0; i < n; ++i)
     a[i] = ((uint64_t)(uint32_t)key_ids[i] << 32) | (uint32_t)other_ids[i];
@@ -504,8 +504,8 @@ int upload_tables(mp_pool *x, const int32_t *src_ids, const int32_t *dst_ids, ui
   int rc = reserve(x, d.tables[slot], std::max<size_t>(8, 8ull * n));
   if (rc != MP_OK) return rc;
   int32_t *h = (int32_t *)d.tables[slot].host;
-  if (sort_by == 0) sort_pairs(x, src_ids, dst_ids, n, key_range, h, h + n);
-  else if (sort_by == 1) sort_pairs(x, dst_ids, src_ids, n, key_range, h + n, h);
+  if (sort_by == 0) sort_pairs(x->sort_a, x->sort_b, src_ids, dst_ids, n, key_range, h, h + n);
+  else if (sort_by == 1) sort_pairs(x->sort_a, x->sort_b, dst_ids, src_ids, n, key_range, h + n, h);
   else {
     if (src_ids) std::memcpy(h, src_ids, 4ull * n);
     if (dst_ids) std::memcpy(h + n, dst_ids, 4ull * n);
@@ -1034,6 +1034,31 @@ int mp_selftest(void) {
         if (fastdiv((uint32_t)v, f) != (uint32_t)v / d) return MP_EINVAL;
       }
     }
+  }
+  // table sorting: both code paths (comparison sort, radix sort) against a reference, key
+  // ranges around the digit boundaries, repeated keys
+  try {
+    std::vector<uint64_t> a, b;
+    uint64_t seed = 88172645463325252ull;
+    auto next = [&]() { seed ^= seed << 13; seed ^= seed >> 7; seed ^= seed << 17; return seed; };
+    for (uint32_t range : {1u, 2u, 2047u, 2048u, 2049u, 40960u, (1u << 22) + 5u, 0x7fffffffu})
+      for (uint32_t n : {0u, 1u, 2u, 511u, 512u, 513u, 5000u}) {
+        std::vector<int32_t> key(n), other(n), ko(n), oo(n);
+        for (uint32_t i = 0; i < n; ++i) {
+          key[i] = (int32_t)(next() % range);
+          other[i] = (int32_t)(next() % 0x7fffffffu);
+        }
+        sort_pairs(a, b, key.data(), other.data(), n, range, ko.data(), oo.data());
+        std::vector<std::pair<int32_t, int32_t>> want(n), got(n);
+        for (uint32_t i = 0; i < n; ++i) want[i] = {key[i], other[i]}, got[i] = {ko[i], oo[i]};
+        for (uint32_t i = 1; i < n; ++i)
+          if (ko[i] < ko[i - 1]) return MP_EINVAL;
+        std::sort(want.begin(), want.end());
+        std::sort(got.begin(), got.end());
+        if (want != got) return MP_EINVAL;  // the same pairs, none lost or split
+      }
+  } catch (...) {
+    return MP_EHOST;
   }
   return MP_OK;
 }
