@@ -24,7 +24,7 @@ import re
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 KINDS = {"0": "gather", "1": "scatter", "2": "fused", "3": "records"}
-OURS = ("kv_block_copy", "plain_copy_kernel", "block_hash_kernel", "block_hash_lanes_kernel",
+OURS = ("kv_block_copy", "plain_copy_kernel", "block_hash_kernel",
         "index_probe_kernel", "index_apply_kernel")
 
 
