@@ -487,6 +487,9 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-per-request", action="store_true", help="skip the per-request figures (C helper + binding)")
     ap.add_argument("--tune", default="", help="comma list key=value for mp_set_tunable")
+    ap.add_argument("--guard-bytes", type=int, default=0,
+                    help="allocate every pool / staging buffer between two canary bands of this many bytes "
+                         "(a multiple of 256); also shifts the buffers against each other")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -511,6 +514,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    TorchPool.GUARD_BYTES = args.guard_bytes
     geom = W.CONFIGS[args.config]
     L, H, D, bs, e = geom.L, geom.H, geom.D, geom.bs, geom.e
     epoch0 = build_epoch(W, geom, args.config, 0)
