@@ -28,14 +28,14 @@ FastDiv make_fastdiv(uint32_t d) {
 }
 
 CopyTune default_tune(CopyTune t, uint64_t frag_bytes, bool both_sides_discrete_pools,
-                      bool dst_is_discrete_pool, bool dst_ids_ascend, bool both_sides_tables) {
+                      bool dst_is_discrete_pool, bool dst_ids_ascend) {
   const bool sweep = dst_is_discrete_pool && dst_ids_ascend;  // stores ascend inside each plane
   if (t.order < 0) t.order = (sweep || both_sides_discrete_pools) ? 1 : 0;
   if (t.plane_tile < 0) t.plane_tile = 0;  // 0: what `order` says
   if (t.unroll < 0) t.unroll = 1;
   if (t.wg_per_cu < 0) t.wg_per_cu = 0;
   if (t.nontemporal < 0) t.nontemporal = 1;
-  if (t.waves_per_wg < 0) t.waves_per_wg = (both_sides_tables && frag_bytes < (64u << 10)) ? 4 : 1;
+  if (t.waves_per_wg < 0) t.waves_per_wg = 1;
   if (t.xcd_contiguous < 0)
     t.xcd_contiguous = (sweep || frag_bytes >= (64u << 10) ||
                         (frag_bytes >= (16u << 10) && dst_is_discrete_pool)) ? 1 : 0;
@@ -223,8 +223,7 @@ CopyTune tune_for(const CopySide &src, const CopySide &dst, bool src_tbl, bool d
   const bool both_discrete = src_tbl && dst_tbl && src.plane_stride > src.block_stride &&
                              dst.plane_stride > dst.block_stride;
   const bool dst_discrete = dst_tbl && dst.plane_stride > dst.block_stride;
-  return default_tune(tune_in, frag_bytes, both_discrete, dst_discrete, dst.ascending,
-                      src_tbl && dst_tbl);
+  return default_tune(tune_in, frag_bytes, both_discrete, dst_discrete, dst.ascending);
 }
 
 Launch prepare(const CopySide &src, const CopySide &dst, bool src_tbl, bool dst_tbl, uint32_t first,

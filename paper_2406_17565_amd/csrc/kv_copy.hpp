@@ -43,11 +43,10 @@ struct CopyTune {
 // destination id), walk plane by plane with each XCD on a contiguous eighth of the items;
 // otherwise walk records when one side is contiguous (staging, an aggregated pool) and planes
 // when both sides are discrete pools; the per-XCD contiguous walk then helps for fragments of
-// 64 KiB and more, and from 16 KiB when the destination is a discrete pool.  The fused copy
-// (a table on both sides) of fragments below 64 KiB is 4 % faster with four waves per workgroup
-// (4 KiB of one fragment stay on one CU); everything else is fastest with one.
+// 64 KiB and more, and from 16 KiB when the destination is a discrete pool.  Waves per
+// workgroup (1 to 16 tried) make no difference once the XCDs walk contiguous ranges; one it is.
 CopyTune default_tune(CopyTune t, uint64_t frag_bytes, bool both_sides_discrete_pools,
-                      bool dst_is_discrete_pool, bool dst_ids_ascend, bool both_sides_tables);
+                      bool dst_is_discrete_pool, bool dst_ids_ascend);
 
 // Unsigned division by an invariant divisor for numerators below 2^31:
 // x / d == (x * m) >> s.
