@@ -27,6 +27,16 @@ def test_header_compiles_as_c_and_host_calls_work():
     assert out.returncode == 0 and "host ok" in out.stdout, out.stdout + out.stderr
 
 
+def test_per_request_bench_program_builds(tmp_path):
+    """bench.py compiles bench_per_request.c at run time on the GPU machine: make sure it builds and
+    links here (C99, warnings as errors), so a typo does not surface only there."""
+    libdir, hip = os.path.dirname(B.LIB), "/opt/rocm/lib"
+    subprocess.check_call(["gcc", "-O2", "-std=c99", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                           os.path.join(ROOT, "bench_per_request.c"), "-o", str(tmp_path / "bench_per_request"),
+                           "-L", libdir, "-lmempool", "-L", hip, "-lamdhip64", f"-Wl,-rpath,{libdir}",
+                           f"-Wl,-rpath,{hip}"])
+
+
 @pytest.mark.gpu
 def test_transfer_from_plain_c():
     if not os.path.exists(EXE):
