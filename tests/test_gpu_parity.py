@@ -226,6 +226,34 @@ def test_transfer_and_errors(gpu, mode):
         p.close()
 
 
+@pytest.mark.parametrize("direct", [0, 1])
+def test_table_sizes_around_the_code_path_switches(gpu, direct):
+    """The copy takes a different route depending on the table length: ids in the kernel
+    arguments up to 192 entries, an uploaded table sorted by comparison up to 512 and by radix
+    sort beyond.  Lengths on both sides of each switch, staged (several rounds included) and
+    fused, every byte against the oracle."""
+    M, TorchPool = gpu
+    geom = GEOMS["f480"]
+    fl = M.MP_DIRECT if direct else 0
+    so, sg = make_pair(gpu, geom, 900, 31, staging_blocks=200)
+    do, dg = make_pair(gpu, geom, 900, 32, staging_blocks=0)
+    assert M.mp_alloc(sg.h, 900)[0] == so.alloc(900)[0] == 0
+    rng = np.random.default_rng(33)
+    for n in (1, 2, 191, 192, 193, 200, 201, 511, 512, 513, 700):
+        tbl = rng.integers(0, 900, n).astype(np.int32)            # sources may repeat
+        rc, d = M.mp_transfer(sg.h, dg.h, tbl, flags=fl | M.MP_ASYNC)
+        rco, d_o = O.transfer(so, do, tbl)
+        assert rc == rco == 0 and d.tolist() == d_o.tolist(), (n, M.mp_last_error(sg.h))
+        given = rng.permutation(d).astype(np.int32)               # explicit, shuffled destinations
+        rc, _ = M.mp_transfer(sg.h, dg.h, tbl, given, flags=fl | M.MP_DST_GIVEN)
+        rco, _ = O.transfer(so, do, tbl, given, flags=O.DST_GIVEN)
+        assert rc == rco == 0
+        _same_state(do, dg)
+        assert M.mp_free(dg.h, d) == do.free(d_o) == 0
+    sg.close()
+    dg.close()
+
+
 def test_transfer_without_staging_is_refused(gpu):
     M, TorchPool = gpu
     geom = GEOMS["f64"]
