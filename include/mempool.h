@@ -26,7 +26,7 @@
  *   data_ptr; for a host pool: pinned host memory) and keeps them alive and 16-byte aligned
  *   until mp_pool_destroy.  The library owns the handle, the host-side index / free list /
  *   reference counts, small device + pinned buffers for block tables, tokens and hashes, one
- *   side stream for host-tier copies, and a few events.  Every pointer argument of every call
+ *   side stream for host-tier copies, one for hashing host-resident tokens, and a few events.  Every pointer argument of every call
  *   below is a HOST pointer unless its comment says "device".
  *
  * BLOCK LIFE CYCLE (paper section 4.1: active vs historical KV cache)
@@ -49,7 +49,10 @@
  * THREADS AND STREAMS
  *   One thread at a time per pool.  Device work of a transfer is enqueued on the SOURCE pool's
  *   stream (the sender executes the transmission, paper section 4.3); hashing for
- *   match/insert runs on the stream of the pool whose index is consulted.  Without MP_ASYNC a
+ *   match/insert of device-resident tokens (MP_TOKENS_ON_DEVICE), and whenever the device probe
+ *   is on, runs on the stream of the pool whose index is consulted; host-resident tokens are
+ *   hashed on a stream of the library's own and the call returns when the hashes are there,
+ *   whatever is still queued on the pool's stream.  Without MP_ASYNC a
  *   call returns after its device work has completed.  With MP_ASYNC a transfer returns once
  *   its work is enqueued: destination ids and the index are already final, the bytes are valid
  *   in the order of the executing stream (the source pool's; the HBM pool's when the source is

@@ -112,7 +112,7 @@ __device__ inline uint64_t block_digest(const uint32_t *__restrict__ t, uint32_t
 __global__ __launch_bounds__(kThreads) void block_hash_kernel(
     const uint32_t *__restrict__ tokens, const uint32_t *__restrict__ tok_off,
     const uint32_t *__restrict__ blk_off, uint32_t bs, uint64_t seed,
-    uint64_t *__restrict__ out) {
+    uint64_t *__restrict__ out, uint32_t *__restrict__ done, uint32_t done_mark) {
   __shared__ uint64_t tile[kTile];
   __shared__ int ready[kTile / 64];  // ready[g] == e: the digests of group g of tile e are in LDS
   const uint32_t r = blockIdx.x;
@@ -165,17 +165,24 @@ __global__ __launch_bounds__(kThreads) void block_hash_kernel(
     }
     __syncthreads();  // the tile and its flags are reused by the next round
   }
+  // Completion mark of this prompt for a host that polls instead of synchronising the stream:
+  // written after the prompt's hashes have left the wave (the fence waits for its stores and
+  // pushes them out at system scope).
+  if (done != nullptr && wave == 0) {
+    __threadfence_system();
+    if (lane == 0) __hip_atomic_store(done + r, done_mark, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+  }
 }
 
 }  // namespace
 
 hipError_t launch_block_hash(const uint32_t *tokens, const uint32_t *tok_off,
                              const uint32_t *blk_off, uint32_t n_req, uint32_t bs, uint64_t seed,
-                             uint64_t *out, hipStream_t stream) {
+                             uint64_t *out, hipStream_t stream, uint32_t *done, uint32_t done_mark) {
   if (n_req == 0) return hipSuccess;
   if (!tok_off || !blk_off || bs == 0) return hipErrorInvalidValue;
   hipLaunchKernelGGL(block_hash_kernel, dim3(n_req), dim3(kThreads), 0, stream, tokens, tok_off,
-                     blk_off, bs, seed, out);
+                     blk_off, bs, seed, out, done, done_mark);
   return hipGetLastError();
 }
 

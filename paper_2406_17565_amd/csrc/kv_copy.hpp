@@ -89,9 +89,12 @@ hipError_t launch_plain_copy(void *dst, const void *src, uint64_t bytes, hipStre
 //   tok_off : device, n_req+1 token offsets
 //   blk_off : device, n_req+1 output offsets (prefix sums of floor(len/bs))
 //   out     : device, blk_off[n_req] hashes
+//   done    : null, or n_req words in host-visible memory: prompt r's word is set to done_mark
+//             (system scope) once its hashes are written, for a host that polls
 hipError_t launch_block_hash(const uint32_t *tokens, const uint32_t *tok_off,
                              const uint32_t *blk_off, uint32_t n_req, uint32_t bs, uint64_t seed,
-                             uint64_t *out, hipStream_t stream);
+                             uint64_t *out, hipStream_t stream, uint32_t *done = nullptr,
+                             uint32_t done_mark = 0);
 
 // Probe of the device-resident index copy for a batch of prompts, right behind the hash kernel.
 //   hashes / hash_off : the chained hashes and their n_req+1 offsets (floor(len/bs) per prompt)

@@ -13,6 +13,8 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
+#include <chrono>
 #include <cstdio>
 #include <cstring>
 #include <mutex>
@@ -58,6 +60,8 @@ struct DeviceCtx {
   int n_cus = 256;
   hipStream_t stream = nullptr;  // the caller's stream (from the pool descriptor)
   hipStream_t side = nullptr;    // library-owned, for pinned-host tier copies
+  hipStream_t hash = nullptr;    // library-owned: hashing of host-resident tokens, which touches
+                                 // no pool memory and so need not queue behind the pool's copies
   // Block tables go up through a small ring of pinned buffers so that asynchronous calls can
   // run ahead of the GPU; the last uploaded pair is remembered, because by-layer transfers
   // repeat one table pair for every layer.
@@ -74,6 +78,8 @@ struct DeviceCtx {
   MirrorBuf tokens;              // concatenated prompts
   MirrorBuf offsets;             // [tok_off][blk_off]
   MirrorBuf hashes;
+  MirrorBuf hash_done;           // pinned: one completion word per prompt, polled by the host
+  uint32_t hash_mark = 0;        // value the words take for the current launch (never 0)
   // the pinned buffers above still hold the last hashed batch: a transfer_with_insert that
   // follows a match of the same prompts reuses the hashes instead of launching again
   bool hash_cache_valid = false;
@@ -163,7 +169,8 @@ bool same_geometry(const mp_pool *a, const mp_pool *b) {
 // ---- device context ----------------------------------------------------------------------
 void destroy_device_objects(DeviceCtx &d) {
   if (d.side) (void)hipStreamDestroy(d.side);
-  d.side = nullptr;
+  if (d.hash) (void)hipStreamDestroy(d.hash);
+  d.side = d.hash = nullptr;
   for (int s = 0; s < DeviceCtx::kTableSlots; ++s) {
     if (d.tables_uploaded[s]) (void)hipEventDestroy(d.tables_uploaded[s]);
     d.tables_uploaded[s] = nullptr;
@@ -185,6 +192,7 @@ int create_device_objects(mp_pool *p) {
   d.n_cus = cus > 0 ? cus : 256;
   d.stream = (hipStream_t)p->desc.stream;
   HIP_TRY(p, hipStreamCreateWithFlags(&d.side, hipStreamNonBlocking));
+  HIP_TRY(p, hipStreamCreateWithFlags(&d.hash, hipStreamNonBlocking));
   for (int s = 0; s < DeviceCtx::kTableSlots; ++s)
     HIP_TRY(p, hipEventCreateWithFlags(&d.tables_uploaded[s], hipEventDisableTiming));
   HIP_TRY(p, hipEventCreateWithFlags(&d.staging_idle, hipEventDisableTiming));
@@ -312,8 +320,8 @@ int device_hashes(mp_pool *p, const uint32_t *tokens, const uint32_t *tok_off, u
   if (total_blk == 0) return MP_OK;
 
   // Offsets, host tokens and the hashes live in pinned host memory that the kernel addresses
-  // directly (zero-copy): a match costs one kernel launch and one stream synchronisation,
-  // no copy-engine commands.  The volumes are tiny (4 B per token in, 8 B per block out).
+  // directly (zero-copy): a match costs one kernel launch and one wait for its completion
+  // words, no copy-engine commands.  The volumes are tiny (4 B per token in, 8 B per block out).
   uint32_t *h_off = (uint32_t *)d.offsets.host;
   std::memcpy(h_off, tok_off, 4ull * (n_req + 1));
   std::memcpy(h_off + n_req + 1, blk_off_out.data(), 4ull * (n_req + 1));
@@ -326,13 +334,48 @@ int device_hashes(mp_pool *p, const uint32_t *tokens, const uint32_t *tok_off, u
     std::memcpy(d.tokens.host, tokens, 4ull * total_tok);
     k_tok = (const uint32_t *)d.tokens.host;
   }
+  // Without a probe kernel behind it, the launch is not waited for with a stream
+  // synchronisation: every prompt's workgroup sets a word in pinned memory when its hashes are
+  // out, and the host polls those words (a few us less per call).  If they do not all turn up
+  // within a generous time the stream is synchronised after all.  Host-resident tokens are
+  // then hashed on a stream of the library's own: the kernel reads and writes pinned host
+  // memory only, so it has no business waiting behind block copies that earlier asynchronous
+  // calls left on the pool's stream.  The host never leaves this function before the kernel
+  // has delivered (or the stream is synchronised), so that stream is idle between calls.
+  const bool poll = !probe_off && !d.profiling;
+  uint32_t *done = nullptr;
+  if (poll) {
+    if ((rc = reserve(p, d.hash_done, 4ull * n_req, false)) != MP_OK) return rc;
+    done = (uint32_t *)d.hash_done.host;
+    if (++d.hash_mark == 0) d.hash_mark = 1;
+    std::memset(done, 0, 4ull * n_req);  // the mark is never 0: no stale or uninitialised word passes
+  }
+  const hipStream_t hs = (poll && !on_device) ? d.hash : d.stream;
   {
     ProfScope ps(p, kProfHash, 4ull * bs * total_blk + 8ull * total_blk);
     HIP_TRY(p, launch_block_hash(k_tok, h_off, h_off + n_req + 1, n_req, bs, p->desc.hash_seed,
-                                 (uint64_t *)d.hashes.host, d.stream));
+                                 (uint64_t *)d.hashes.host, hs, done, d.hash_mark));
   }
   if (probe_off && (rc = launch_probe(p, k_tok, n_req, probe_off)) != MP_OK) return rc;
-  HIP_TRY(p, hipStreamSynchronize(d.stream));
+  bool seen = false;
+  if (poll) {
+    const volatile uint32_t *w = done;
+    const auto t_end = std::chrono::steady_clock::now() + std::chrono::milliseconds(20);
+    uint32_t r = 0;
+    for (uint32_t spin = 0;; ++spin) {
+      while (r < n_req && w[r] == d.hash_mark) ++r;
+      if (r == n_req) {
+        seen = true;
+        break;
+      }
+      if ((spin & 1023u) == 1023u && std::chrono::steady_clock::now() > t_end) break;
+      __builtin_ia32_pause();
+    }
+    std::atomic_thread_fence(std::memory_order_acquire);
+  }
+  // device-resident tokens were also copied back on this stream in front of the kernel: in
+  // stream order that copy is complete once the kernel has run
+  if (!seen) HIP_TRY(p, hipStreamSynchronize(hs));
   d.hash_cache_valid = !on_device;
   d.hash_cache_n_req = n_req;
   return MP_OK;
@@ -1100,6 +1143,7 @@ int mp_pool_destroy(mp_pool_t *p) {
     release(d.tokens);
     release(d.offsets);
     release(d.hashes);
+    release(d.hash_done);
     mirror_disable(p);
     release(d.m_updates);
     release(d.m_out);

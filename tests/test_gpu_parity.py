@@ -625,6 +625,45 @@ def test_async_and_callback(gpu):
     dg.close()
 
 
+def test_match_and_insert_while_copies_are_still_queued(gpu):
+    """Prompts in host memory are hashed on a stream of the library's own and waited for through
+    completion words, not through the pool's stream: with asynchronous copies still queued on
+    both pools' streams, insert, match and the hashes return the oracle's results, and the
+    queued copies land untouched."""
+    M, TorchPool = gpu
+    geom = GEOMS["f32k"]                                   # 256 KiB blocks
+    NB = 768
+    so, sg = make_pair(gpu, geom, NB, 11, staging_blocks=NB)
+    do, dg = make_pair(gpu, geom, NB, 12, staging_blocks=0)
+    M.mp_alloc(sg.h, NB)
+    so.alloc(NB)
+    rng = np.random.default_rng(5)
+    tbl = W.random_table(rng, NB, 700)
+    rc, d = M.mp_transfer(sg.h, dg.h, tbl, flags=M.MP_ASYNC)
+    rco, d_o = O.transfer(so, do, tbl)
+    assert rc == rco == 0 and d.tolist() == d_o.tolist()
+    bs, at = geom[3], 0
+    for k in range(6):                                     # more copies behind it, then the index calls
+        fl = M.MP_ASYNC | M.MP_DST_GIVEN | (M.MP_DIRECT if k & 1 else 0)
+        assert M.mp_transfer(sg.h, dg.h, tbl, d, flags=fl)[0] == 0
+        t = rng.integers(0, 128256, (30 + 25 * k) * bs + k, dtype=np.uint32)
+        nb = len(t) // bs
+        ids = d[at:at + nb]
+        at += nb
+        rc, n_new = M.mp_insert(dg.h, t, ids)
+        rco, n_o = do.insert(t, ids)
+        assert rc == rco == 0 and n_new == n_o == nb, M.mp_last_error(dg.h)
+        rc, m = M.mp_match(dg.h, t, nb + 4)
+        rco, mo = do.match(t)
+        assert rc == rco == 0 and m.tolist() == mo.tolist() == ids.tolist()
+        rc, h = M.mp_block_hashes(dg.h, t[bs:], bs)
+        assert rc == 0 and np.array_equal(h, O.block_hashes(t[bs:], bs, 0))
+    torch.cuda.synchronize()
+    _same_state(do, dg)
+    sg.close()
+    dg.close()
+
+
 def test_profile_counters(gpu):
     M, TorchPool = gpu
     geom = GEOMS["f32k"]
