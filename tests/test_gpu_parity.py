@@ -79,6 +79,25 @@ def test_block_hashes_batch(gpu):
     p.close()
 
 
+def test_block_hashes_of_many_prompts_in_a_row(gpu):
+    """Thousands of prompts per launch, many of them empty or shorter than a block, then smaller
+    batches on the same pool: every launch reports per prompt, and no report of an earlier launch
+    may pass for a later one."""
+    M, TorchPool = gpu
+    bs = 8
+    rng = np.random.default_rng(78)
+    p = TorchPool(1, 1, 8, bs, 2, 4, seed=9)
+    for n_req in (3000, 3000, 700, 1, 64, 2999):
+        lens = rng.choice([0, 3, bs, 5 * bs + 1, 40 * bs, 130 * bs + 7], n_req, p=[.2, .1, .2, .3, .15, .05])
+        prompts = [rng.integers(0, 2**32, int(n), dtype=np.uint32) for n in lens]
+        toks, tok_off = W.csr(prompts)
+        rc, h, hoff = M.mp_block_hashes_batch(p.h, toks, tok_off, bs)
+        assert rc == 0, M.mp_last_error(p.h)
+        want = np.concatenate([O.block_hashes(t, bs, 9) for t in prompts] + [np.zeros(0, np.uint64)])
+        assert np.array_equal(h, want), n_req
+    p.close()
+
+
 def test_block_hashes_golden(gpu, golden_dir):
     M, TorchPool = gpu
     import os
