@@ -282,6 +282,43 @@ void prof_drain(mp_pool *p) {
 // the n_req+1 offsets into that array.  Host tokens are copied into pinned memory; device
 // tokens are also copied back, because index nodes keep (and compare) their tokens.
 // On return *host_tokens points at a host copy of all tokens.
+// The completion words of one hash launch, for a caller that wants to use the hashes of the
+// first prompts while the later ones are still being computed.  Whoever holds one must not
+// return to the library's caller before everything has arrived: the destructor sees to that.
+struct HashWait {
+  mp_pool *p = nullptr;
+  const volatile uint32_t *words = nullptr;  // null: nothing (or nothing any more) to wait for
+  uint32_t mark = 0, n_req = 0, next = 0;    // prompts [0, next) have reported
+  hipStream_t hs = nullptr;
+  std::chrono::steady_clock::time_point give_up;
+  // Returns once the hashes of prompts 0..r are in host memory.  A launch that has not
+  // reported by `give_up` is waited for with a stream synchronisation instead.
+  int upto(uint32_t r) {
+    if (!words) return MP_OK;
+    for (uint32_t spin = 0; next <= r; ++spin) {
+      while (next < n_req && words[next] == mark) ++next;
+      if (next > r) break;
+      if ((spin & 1023u) == 1023u && std::chrono::steady_clock::now() > give_up) {
+        words = nullptr;
+        const hipError_t e = hipStreamSynchronize(hs);
+        if (e == hipSuccess) return MP_OK;
+        p->dev.hash_cache_valid = false;  // what the pinned buffers hold is not to be reused
+        return fail_hip(p, e, "hipStreamSynchronize(hash stream)");
+      }
+      __builtin_ia32_pause();
+    }
+    std::atomic_thread_fence(std::memory_order_acquire);
+    if (next == n_req) words = nullptr;
+    return MP_OK;
+  }
+  HashWait() = default;
+  HashWait(const HashWait &) = delete;
+  HashWait &operator=(const HashWait &) = delete;
+  ~HashWait() {
+    if (words && n_req) (void)upto(n_req - 1);
+  }
+};
+
 int mirror_sync(mp_pool *p);
 int launch_probe(mp_pool *p, const uint32_t *k_tok, uint32_t n_req, const uint32_t *probe_off);
 
@@ -290,7 +327,7 @@ int launch_probe(mp_pool *p, const uint32_t *k_tok, uint32_t n_req, const uint32
 int device_hashes(mp_pool *p, const uint32_t *tokens, const uint32_t *tok_off, uint32_t n_req,
                   bool on_device, std::vector<uint32_t> &blk_off_out,
                   const uint32_t **host_tokens, const uint64_t **host_hashes,
-                  const uint32_t *probe_off = nullptr) {
+                  const uint32_t *probe_off = nullptr, HashWait *defer = nullptr) {
   int rc = ensure_device(p);
   if (rc != MP_OK) return rc;
   DeviceCtx &d = p->dev;
@@ -340,8 +377,9 @@ int device_hashes(mp_pool *p, const uint32_t *tokens, const uint32_t *tok_off, u
   // within a generous time the stream is synchronised after all.  Host-resident tokens are
   // then hashed on a stream of the library's own: the kernel reads and writes pinned host
   // memory only, so it has no business waiting behind block copies that earlier asynchronous
-  // calls left on the pool's stream.  The host never leaves this function before the kernel
-  // has delivered (or the stream is synchronised), so that stream is idle between calls.
+  // calls left on the pool's stream.  The host never returns to the library's caller before the
+  // kernel has delivered (or the stream is synchronised), so that stream is idle between calls.
+  // With `defer` the waiting is left to the caller of this function, prompt by prompt.
   const bool poll = !probe_off && !d.profiling;
   uint32_t *done = nullptr;
   if (poll) {
@@ -357,28 +395,27 @@ int device_hashes(mp_pool *p, const uint32_t *tokens, const uint32_t *tok_off, u
                                  (uint64_t *)d.hashes.host, hs, done, d.hash_mark));
   }
   if (probe_off && (rc = launch_probe(p, k_tok, n_req, probe_off)) != MP_OK) return rc;
-  bool seen = false;
-  if (poll) {
-    const volatile uint32_t *w = done;
-    const auto t_end = std::chrono::steady_clock::now() + std::chrono::milliseconds(20);
-    uint32_t r = 0;
-    for (uint32_t spin = 0;; ++spin) {
-      while (r < n_req && w[r] == d.hash_mark) ++r;
-      if (r == n_req) {
-        seen = true;
-        break;
-      }
-      if ((spin & 1023u) == 1023u && std::chrono::steady_clock::now() > t_end) break;
-      __builtin_ia32_pause();
-    }
-    std::atomic_thread_fence(std::memory_order_acquire);
+  // (device-resident tokens were also copied back on this stream in front of the kernel: in
+  // stream order that copy is complete once the kernel has run)
+  if (!poll) {
+    HIP_TRY(p, hipStreamSynchronize(hs));
+    d.hash_cache_valid = !on_device;
+    d.hash_cache_n_req = n_req;
+    return MP_OK;
   }
-  // device-resident tokens were also copied back on this stream in front of the kernel: in
-  // stream order that copy is complete once the kernel has run
-  if (!seen) HIP_TRY(p, hipStreamSynchronize(hs));
+  // the remembered batch is consulted by later calls only, and none starts before the wait is over
   d.hash_cache_valid = !on_device;
   d.hash_cache_n_req = n_req;
-  return MP_OK;
+  HashWait here;
+  HashWait &w = defer ? *defer : here;
+  w.p = p;
+  w.words = done;
+  w.mark = d.hash_mark;
+  w.n_req = n_req;
+  w.next = 0;
+  w.hs = hs;
+  w.give_up = std::chrono::steady_clock::now() + std::chrono::milliseconds(20);
+  return defer ? MP_OK : w.upto(n_req - 1);
 }
 
 // ---- device-resident index copy ----------------------------------------------------------------
@@ -1318,10 +1355,14 @@ int mp_match_batch(mp_pool_t *p, const uint32_t *tokens, const uint32_t *tok_off
       }
       return MP_OK;
     }
+    // the index walk of a prompt starts as soon as its hashes are there, while the kernel is
+    // still busy with longer prompts
+    HashWait arriving;
     int rc = device_hashes(p, tokens, tok_off, n_req, (flags & MP_TOKENS_ON_DEVICE) != 0, hoff, &htok,
-                           &hh);
+                           &hh, nullptr, &arriving);
     if (rc != MP_OK) return rc;
     for (uint32_t r = 0; r < n_req; ++r) {
+      if ((rc = arriving.upto(r)) != MP_OK) return rc;
       const uint32_t nb = std::min(hoff[r + 1] - hoff[r], blk_off[r + 1] - blk_off[r]);
       match_walk(p, htok + tok_off[r], hh + hoff[r], nb, blocks_out + blk_off[r], &n_matched_out[r],
                  flags);
