@@ -197,6 +197,48 @@ def test_config3_multiturn_sessions(gpu):
     release(src, dst)
 
 
+@pytest.mark.parametrize("direct", [0, 1])
+def test_config3_one_call_per_request(gpu, direct):
+    """The per-request flavour bench.py also times, at the full pool size: mp_match (pin) and one
+    asynchronous mp_transfer_with_insert per request -- 24-50 blocks each, so the block ids travel
+    in the kernel arguments -- staged and fused, every entry and plane checked per request."""
+    M, TorchPool = gpu
+    g = W.CONFIGS[3]
+    geom, src, dst = make_pools(gpu, g, g.NB, g.NB, staging_blocks=64)
+    mir = Mirror(g.bs, g.NB, g.NB)
+    rng = np.random.default_rng(34 + direct)
+    sessions = W.multiturn_sessions(seed=3)
+    flags = M.MP_EVICT_ON_DEMAND | M.MP_ASYNC | (M.MP_DIRECT if direct else 0)
+    before = checksums(dst)
+    touched = torch.zeros(g.NB, dtype=torch.bool, device="cuda")
+    for t in range(2):
+        perm = rng.permutation(g.NB).astype(np.int32)
+        at = 0
+        for s in range(0, 64, 3):                                   # 22 requests per turn
+            p = sessions[s][t]
+            nblk = (len(p) + g.bs - 1) // g.bs
+            rc, m = M.mp_match(dst.h, p, nblk, M.MP_MATCH_PIN)
+            rco, mo = mir.dst.match(p, flags=O.MATCH_PIN)
+            assert rc == rco == 0 and m.tolist() == mo.tolist()
+            n = nblk - len(m)
+            assert 0 < n <= 192
+            src_tbl = perm[at:at + n]
+            at += n
+            rc, d = M.mp_transfer_with_insert(src.h, dst.h, p, len(m), src_tbl, flags=flags)
+            assert rc == 0, M.mp_last_error(src.h)
+            rco, d_o = O.transfer_with_insert(mir.src, mir.dst, p, len(mo), src_tbl, flags=O.EVICT_ON_DEMAND)
+            assert rco == 0 and d.tolist() == d_o.tolist()
+            check_all_entries(src, dst, src_tbl, d)
+            if s % 12 == 0:
+                check_sample(geom, src, dst, src_tbl, d, rng, k=8)
+            touched[torch.as_tensor(d.astype(np.int64), device="cuda")] = True
+            assert dst.stats() == mir.dst.stats()
+    after = checksums(dst)
+    assert torch.equal(before[:, ~touched], after[:, ~touched])      # nothing else was written
+    assert int(touched.sum()) > 800
+    release(src, dst)
+
+
 def test_config2_lognormal_requests(gpu):
     """Llama-2-7B shape (128 KiB fragments), 8192-block pools (64 GiB each), 16 requests with
     log-normal lengths, fragmented tables; per-request calls and one batched call."""
