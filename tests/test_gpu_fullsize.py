@@ -239,6 +239,46 @@ def test_config3_one_call_per_request(gpu, direct):
     release(src, dst)
 
 
+@pytest.mark.parametrize("direct", [0, 1])
+def test_config3_layer_by_layer(gpu, direct):
+    """mp_transfer_layers at the full pool size with a turn-sized table (the by-layer mode bench.py
+    times): layer ranges of one, two and five layers into explicit destinations; the planes of
+    the moved layers equal the source's for every entry, every other plane and block is unchanged."""
+    M, TorchPool = gpu
+    g = W.CONFIGS[3]
+    geom, src, dst = make_pools(gpu, g, g.NB, g.NB, staging_blocks=64 * 50)
+    rng = np.random.default_rng(36 + direct)
+    n = 2300
+    rc, d = M.mp_alloc(dst.h, n)
+    assert rc == 0
+    src_sums = checksums(src)
+    flags = M.MP_ASYNC | (M.MP_DIRECT if direct else 0)
+    for l0, l1 in ((0, 1), (13, 15), (27, 32), (31, 32)):
+        src_tbl = rng.permutation(g.NB)[:n].astype(np.int32)
+        before = checksums(dst)
+        pick = rng.choice(n, size=6, replace=False)
+        src_blocks, dst_before = blocks_of(src, src_tbl[pick]), blocks_of(dst, d[pick])
+        assert M.mp_transfer_layers(src.h, dst.h, src_tbl, d, l0, l1, flags) == 0, M.mp_last_error(src.h)
+        torch.cuda.synchronize()
+        after = checksums(dst)
+        # the sampled entries through the oracle's own by-layer transfer, byte for byte
+        L, H, D, bs, e = geom
+        as_pool = lambda blocks: np.ascontiguousarray(blocks.transpose(1, 0, 2)).reshape(-1)
+        o_src = O.OraclePool(L, H, D, bs, e, 6, data=as_pool(src_blocks))
+        o_dst = O.OraclePool(L, H, D, bs, e, 6, data=as_pool(dst_before))
+        o_src.alloc(6)
+        o_dst.alloc(6)
+        assert O.transfer_layers(o_src, o_dst, np.arange(6), np.arange(6), l0, l1) == 0
+        assert np.array_equal(blocks_of(dst, d[pick]), o_dst.data.reshape(2 * L, 6, src.F).transpose(1, 0, 2))
+        si = torch.as_tensor(src_tbl.astype(np.int64), device="cuda")
+        di = torch.as_tensor(d.astype(np.int64), device="cuda")
+        want = before.clone()
+        want[2 * l0:2 * l1, di] = src_sums[2 * l0:2 * l1][:, si]
+        bad = (want != after).nonzero()
+        assert bad.numel() == 0, f"{bad.shape[0]} fragments differ, first (plane, block) = {bad[0].tolist()}"
+    release(src, dst)
+
+
 def test_config2_lognormal_requests(gpu):
     """Llama-2-7B shape (128 KiB fragments), 8192-block pools (64 GiB each), 16 requests with
     log-normal lengths, fragmented tables; per-request calls and one batched call."""
