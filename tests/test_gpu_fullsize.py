@@ -97,10 +97,10 @@ def blocks_of(pool, ids):
     """[len(ids), 2L, F] bytes of the given blocks, on the host."""
     L2 = 2 * pool.geom[0]
     idx = torch.as_tensor(np.asarray(ids, dtype=np.int64), device=pool.mem.device)
-    if pool.tier == 0:
+    if not pool.aggregated:
         x = pool.mem.view(L2, pool.NB, pool.F)[:, idx, :].permute(1, 0, 2)
     else:
-        x = pool.mem.view(pool.NB, L2, pool.F)[idx.cpu()]
+        x = pool.mem.view(pool.NB, L2, pool.F)[idx]
     return x.contiguous().cpu().numpy()
 
 
@@ -136,12 +136,12 @@ class Mirror:
         self.src.alloc(NB_src)
 
 
-def make_pools(gpu, g, NB_src, NB_dst, staging_blocks):
+def make_pools(gpu, g, NB_src, NB_dst, staging_blocks, layouts=(0, 0)):
     M, TorchPool = gpu
     geom = (g.L, g.H, g.D, g.bs, g.e)
     s_src, s_dst = torch.cuda.Stream(), torch.cuda.Stream()
-    src = TorchPool(*geom, NB_src, staging_blocks=staging_blocks, stream=s_src)
-    dst = TorchPool(*geom, NB_dst, stream=s_dst)
+    src = TorchPool(*geom, NB_src, staging_blocks=staging_blocks, stream=s_src, layout=layouts[0])
+    dst = TorchPool(*geom, NB_dst, stream=s_dst, layout=layouts[1])
     fill_random(src)
     fill_random(dst)
     assert M.mp_alloc(src.h, NB_src)[0] == 0
@@ -276,6 +276,30 @@ def test_config3_layer_by_layer(gpu, direct):
         want[2 * l0:2 * l1, di] = src_sums[2 * l0:2 * l1][:, si]
         bad = (want != after).nonzero()
         assert bad.numel() == 0, f"{bad.shape[0]} fragments differ, first (plane, block) = {bad[0].tolist()}"
+    release(src, dst)
+
+
+@pytest.mark.parametrize("layouts,direct", [((2, 2), 0), ((2, 0), 1), ((0, 2), 0), ((2, 2), 1)])
+def test_config3_aggregated_pools(gpu, layouts, direct):
+    """HBM pools in the aggregated layout (one or both ends) at the full size of config 3: one
+    turn-sized asynchronous transfer; every entry and plane, and everything outside the table."""
+    M, TorchPool = gpu
+    g = W.CONFIGS[3]
+    geom, src, dst = make_pools(gpu, g, g.NB, g.NB, staging_blocks=2400, layouts=layouts)
+    rng = np.random.default_rng(40 + direct)
+    mir = Mirror(g.bs, g.NB, g.NB)
+    for n in (2300, 1266):
+        src_tbl = rng.permutation(g.NB)[:n].astype(np.int32)
+        before = checksums(dst)
+        rc, d = M.mp_transfer(src.h, dst.h, src_tbl, flags=M.MP_ASYNC | (M.MP_DIRECT if direct else 0))
+        rco, d_o = O.transfer(mir.src, mir.dst, src_tbl)
+        assert rc == rco == 0 and d.tolist() == d_o.tolist(), M.mp_last_error(src.h)
+        check_sample(geom, src, dst, src_tbl, d, rng, k=8)
+        after = checksums(dst)
+        check_all_entries(src, dst, src_tbl, d, dst_sums=after)
+        untouched = torch.ones(g.NB, dtype=torch.bool, device="cuda")
+        untouched[torch.as_tensor(d.astype(np.int64), device="cuda")] = False
+        assert torch.equal(before[:, untouched], after[:, untouched])
     release(src, dst)
 
 
