@@ -1175,6 +1175,7 @@ int mp_pool_destroy(mp_pool_t *p) {
   if (d.ready) {
     (void)hipStreamSynchronize(d.stream);
     (void)hipStreamSynchronize(d.side);
+    (void)hipStreamSynchronize(d.hash);
     prof_drain(p);
     for (int s = 0; s < DeviceCtx::kTableSlots; ++s) release(d.tables[s]);
     release(d.tokens);
@@ -1608,63 +1609,66 @@ int mp_transfer_static(mp_pool_t *src, mp_pool_t *dst, const int32_t *src_blocks
   // No allocation of any kind on this path: no hipMalloc / hipFree / hipHostMalloc, no stream or
   // event creation, no std::vector growth.
   if (!src || !dst) return MP_EINVAL;
-  if ((!src_blocks || !dst_blocks) && n) return fail(src, MP_EINVAL, "null block table");
-  if (flags & ~(MP_DST_GIVEN | MP_ASYNC | MP_DIRECT))
-    return fail(src, MP_EINVAL, "mp_transfer_static takes MP_ASYNC and MP_DIRECT only");
-  if (n > MP_STATIC_MAX_BLOCKS)
-    return fail(src, MP_EINVAL, "more than MP_STATIC_MAX_BLOCKS (65536) table entries");
-  if (!same_geometry(src, dst)) return fail(src, MP_ESHAPE, "source and destination geometry differ");
-  if (src->desc.tier != MP_TIER_HBM || dst->desc.tier != MP_TIER_HBM)
-    return fail(src, MP_ESHAPE, "mp_transfer_static moves blocks between HBM pools only");
-  int rc = check_src_ids(src, src_blocks, n);
-  if (rc != MP_OK) return rc;
-  if (!dst->idx.held_and_distinct(dst_blocks, n))
-    return fail(src, MP_EINVAL, "destination ids must be held and distinct");
-  const bool direct = (flags & MP_DIRECT) != 0;
-  if (!direct && n && (!src->desc.staging || src->desc.staging_bytes < src->B))
-    return fail(src, MP_ENOSTAGING, "staging buffer missing or smaller than one record");
-  if ((rc = check_same_pool(src, dst, src_blocks, dst_blocks, n, flags | MP_DST_GIVEN)) != MP_OK)
-    return rc;
-  if (n == 0) return MP_OK;
+  try {
+    if ((!src_blocks || !dst_blocks) && n) return fail(src, MP_EINVAL, "null block table");
+    if (flags & ~(MP_DST_GIVEN | MP_ASYNC | MP_DIRECT))
+      return fail(src, MP_EINVAL, "mp_transfer_static takes MP_ASYNC and MP_DIRECT only");
+    if (n > MP_STATIC_MAX_BLOCKS)
+      return fail(src, MP_EINVAL, "more than MP_STATIC_MAX_BLOCKS (65536) table entries");
+    if (!same_geometry(src, dst)) return fail(src, MP_ESHAPE, "source and destination geometry differ");
+    if (src->desc.tier != MP_TIER_HBM || dst->desc.tier != MP_TIER_HBM)
+      return fail(src, MP_ESHAPE, "mp_transfer_static moves blocks between HBM pools only");
+    int rc = check_src_ids(src, src_blocks, n);
+    if (rc != MP_OK) return rc;
+    if (!dst->idx.held_and_distinct(dst_blocks, n))
+      return fail(src, MP_EINVAL, "destination ids must be held and distinct");
+    const bool direct = (flags & MP_DIRECT) != 0;
+    if (!direct && n && (!src->desc.staging || src->desc.staging_bytes < src->B))
+      return fail(src, MP_ENOSTAGING, "staging buffer missing or smaller than one record");
+    if ((rc = check_same_pool(src, dst, src_blocks, dst_blocks, n, flags | MP_DST_GIVEN)) != MP_OK)
+      return rc;
+    if (n == 0) return MP_OK;
 
-  int dev = 0;
-  HIP_TRY(src, hipGetDevice(&dev));
-  if (dev < 0 || dev >= kMaxDevices) return fail(src, MP_EINVAL, "device ordinal out of range");
-  int32_t *tables = nullptr;
-  {
-    std::lock_guard<std::mutex> lock(g_static_mutex);
-    if (!g_static_tables[dev])  // once per device, with that device current
-      HIP_TRY(src, hipGetSymbolAddress((void **)&g_static_tables[dev], HIP_SYMBOL(scratch)));
-    tables = g_static_tables[dev];
-  }
-  if (!tables) return fail(src, MP_EHIP, "no device address for the static block tables");
-
-  // Both tables go up on the executing stream, so they are ordered behind the kernels of an
-  // earlier call on the same stream that still read the array.
-  hipStream_t stream = (hipStream_t)src->desc.stream;
-  int32_t *d_src = tables, *d_dst = tables + MP_STATIC_MAX_BLOCKS;
-  HIP_TRY(src, hipMemcpyAsync(d_src, src_blocks, 4ull * n, hipMemcpyHostToDevice, stream));
-  HIP_TRY(src, hipMemcpyAsync(d_dst, dst_blocks, 4ull * n, hipMemcpyHostToDevice, stream));
-  const int n_cus = src->dev.n_cus;
-  bool ascends = true;  // nothing is sorted here (no host buffer to sort into): take what the caller gives
-  for (uint32_t i = 1; i < n && ascends; ++i) ascends = dst_blocks[i] > dst_blocks[i - 1];
-  if (direct) {
-    HIP_TRY(src, launch_block_copy(pool_side(src, d_src), pool_side(dst, d_dst, 0, ascends), n, src->P,
-                                   src->F, src->tune, n_cus, stream));
-  } else {
-    const uint32_t cap = (uint32_t)std::min<uint64_t>(src->desc.staging_bytes / src->B, 0xffffffffu);
-    for (uint32_t first = 0; first < n; first += cap) {
-      const uint32_t cnt = std::min(cap, n - first);
-      HIP_TRY(src, launch_block_copy(pool_side(src, d_src + first),
-                                     record_side(src, src->desc.staging, src->P), cnt, src->P, src->F,
-                                     src->tune, n_cus, stream));
-      HIP_TRY(src, launch_block_copy(record_side(src, src->desc.staging, src->P),
-                                     pool_side(dst, d_dst + first, 0, ascends), cnt, src->P, src->F,
-                                     src->tune, n_cus, stream));
+    int dev = 0;
+    HIP_TRY(src, hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(src, MP_EINVAL, "device ordinal out of range");
+    int32_t *tables = nullptr;
+    {
+      std::lock_guard<std::mutex> lock(g_static_mutex);
+      if (!g_static_tables[dev])  // once per device, with that device current
+        HIP_TRY(src, hipGetSymbolAddress((void **)&g_static_tables[dev], HIP_SYMBOL(scratch)));
+      tables = g_static_tables[dev];
     }
+    if (!tables) return fail(src, MP_EHIP, "no device address for the static block tables");
+
+    // Both tables go up on the executing stream, so they are ordered behind the kernels of an
+    // earlier call on the same stream that still read the array.
+    hipStream_t stream = (hipStream_t)src->desc.stream;
+    int32_t *d_src = tables, *d_dst = tables + MP_STATIC_MAX_BLOCKS;
+    HIP_TRY(src, hipMemcpyAsync(d_src, src_blocks, 4ull * n, hipMemcpyHostToDevice, stream));
+    HIP_TRY(src, hipMemcpyAsync(d_dst, dst_blocks, 4ull * n, hipMemcpyHostToDevice, stream));
+    const int n_cus = src->dev.n_cus;
+    bool ascends = true;  // nothing is sorted here (no host buffer to sort into): take what the caller gives
+    for (uint32_t i = 1; i < n && ascends; ++i) ascends = dst_blocks[i] > dst_blocks[i - 1];
+    if (direct) {
+      HIP_TRY(src, launch_block_copy(pool_side(src, d_src), pool_side(dst, d_dst, 0, ascends), n, src->P,
+                                     src->F, src->tune, n_cus, stream));
+    } else {
+      const uint32_t cap = (uint32_t)std::min<uint64_t>(src->desc.staging_bytes / src->B, 0xffffffffu);
+      for (uint32_t first = 0; first < n; first += cap) {
+        const uint32_t cnt = std::min(cap, n - first);
+        HIP_TRY(src, launch_block_copy(pool_side(src, d_src + first),
+                                       record_side(src, src->desc.staging, src->P), cnt, src->P, src->F,
+                                       src->tune, n_cus, stream));
+        HIP_TRY(src, launch_block_copy(record_side(src, src->desc.staging, src->P),
+                                       pool_side(dst, d_dst + first, 0, ascends), cnt, src->P, src->F,
+                                       src->tune, n_cus, stream));
+      }
+    }
+    if (!(flags & MP_ASYNC)) HIP_TRY(src, hipStreamSynchronize(stream));
+    return MP_OK;
   }
-  if (!(flags & MP_ASYNC)) HIP_TRY(src, hipStreamSynchronize(stream));
-  return MP_OK;
+  MP_CATCH(src)
 }
 
 int mp_gather(mp_pool_t *p, const int32_t *tbl, uint32_t n, uint32_t flags) {
